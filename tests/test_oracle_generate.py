@@ -1,0 +1,199 @@
+"""Pins for oracle/generate.py, search.py and cost.py: lower bounds, table rows and exhaustive search."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from conftest import read_examples, read_table
+from oracle import collective as col
+from oracle import cost
+from oracle import generate as gen
+from oracle import search
+from oracle import topology as tp
+from oracle.schedule import COPY, REDUCE, Schedule
+from oracle.validate import Verdict, validate
+
+T4 = read_table("table4_dgx1.txt")
+T5 = read_table("table5_z52.txt")
+
+
+def check_allgather(topo, C, sched):
+    ag = col.allgather(topo.num_nodes, C)
+    rep = validate(topo, ag, sched)
+    assert rep.ok, rep.detail
+    assert sched.num_steps >= tp.diameter(topo)                                        # a_l of Algorithm 1
+    assert Fraction(sched.num_rounds, C) >= tp.allgather_bandwidth_bound(topo)         # ingress argument, section 2.4
+    # one receive per (chunk, node) outside pre: P*C*(P-1) sends, each chunk a tree
+    P = topo.num_nodes
+    assert sched.sends.shape[0] == P * C * (P - 1)
+    assert len({(c, m) for (c, n, m, s, op) in sched.sends.tolist()}) == P * C * (P - 1)
+    return rep
+
+
+def test_config1_ring4_is_latency_optimal():
+    s = gen.greedy_bfs(tp.ring(4), col.allgather(4, 1))
+    check_allgather(tp.ring(4), 1, s)
+    assert (s.num_steps, s.num_rounds, s.sends.shape[0]) == (2, 2, 12)
+
+
+@pytest.mark.parametrize("topo,C", [
+    (tp.hcm8(), 1), (tp.hcm8(), 2), (tp.dgx1(), 1), (tp.dgx1(), 2), (tp.ring(8), 1), (tp.ring(8), 2),
+    (tp.torus2d(4, 4), 1), (tp.torus2d(4, 4), 4), (tp.complete(5), 1), (tp.ring(5), 3),
+])
+def test_greedy_allgather_is_valid_and_respects_the_bounds(topo, C):
+    s = gen.greedy_bfs(topo, col.allgather(topo.num_nodes, C))
+    check_allgather(topo, C, s)
+    assert all(r == 1 for r in s.rounds)
+
+
+def test_torus_config_needs_at_least_15_steps():
+    topo = tp.torus2d(4, 4)
+    s = gen.greedy_bfs(topo, col.allgather(16, 4))
+    assert s.num_steps >= 15              # 60 chunks in over 4 unit links
+    assert s.sends.shape[0] == 960
+
+
+def test_feasible_rows_of_the_tables_are_reached():
+    # Table 4: Allgather (1,2,2) exists on the DGX-1 graph; Table 5: (1,4,4) on the 8-ring
+    assert ("allgather", 1, 2, 2) in [r[:4] for r in T4]
+    s = gen.greedy_bfs(tp.dgx1(), col.allgather(8, 1))
+    assert s.csr(1) == (1, 2, 2)
+    assert ("allgather", 1, 4, 4) in [r[:4] for r in T5]
+    s = gen.greedy_bfs(tp.ring(8), col.allgather(8, 1))
+    assert s.csr(1) == (1, 4, 4)
+    # the benchmark's own 8-node graph also admits two steps with one chunk per node
+    s = gen.greedy_bfs(tp.hcm8(), col.allgather(8, 1))
+    assert s.csr(1) == (1, 2, 2)
+
+
+def test_ring_generator_reproduces_table5_row():
+    assert ("allgather", 2, 7, 7) in [r[:4] for r in T5]
+    s = gen.ring_allgather(8, 2)
+    check_allgather(tp.ring(8), 2, s)
+    assert s.csr(2) == (2, 7, 7)
+    assert Fraction(s.num_rounds, 2) == tp.allgather_bandwidth_bound(tp.ring(8))      # bandwidth optimal
+    ar, arc = gen.compose_allreduce(s, col.allgather(8, 2))
+    assert validate(tp.ring(8), arc, ar).ok
+    assert ("allreduce",) + ar.csr(arc.num_chunks) in [r[:4] for r in T5]             # (16,14,14)
+
+
+def test_ring_generator_config4_reading():
+    # two chunks per rank per direction: C = 4, two rounds per step, 14 steps as Allreduce
+    s = gen.ring_allgather(8, 4)
+    check_allgather(tp.ring(8), 4, s)
+    assert s.rounds == [2] * 7
+    ar, arc = gen.compose_allreduce(s, col.allgather(8, 4))
+    assert validate(tp.ring(8), arc, ar).ok
+    assert (arc.num_chunks, ar.num_steps, ar.num_rounds, ar.sends.shape[0]) == (32, 14, 28, 448)
+
+
+def test_six_ring_example_of_section_2_4():
+    # DGX-1 as six logical rings: C = 6, 7 steps; on ONE 8-ring with unit links that is 3 rounds per step,
+    # on the DGX-1's six rings one round: the (C,S,R) the paper attributes to NCCL
+    ex = read_examples()
+    C, S, R = map(int, ex["nccl_dgx1_allgather"])
+    assert cost.cost_pair(C, S, R) == (7, Fraction(7, 6))
+    assert tuple(map(int, ex["nccl_dgx1_allreduce"])) == (8 * C, 2 * S, 2 * R)
+
+
+def test_cost_model_matches_every_printed_running_time():
+    for (name, C, S, R, a, b, opt) in T4 + T5:
+        assert cost.cost_pair(C, S, R) == (a, b), (name, C, S, R)
+    ex = read_examples()
+    assert (int(ex["synth_dgx1_bw_optimal_cost"][0]), Fraction(ex["synth_dgx1_bw_optimal_cost"][1])) == cost.cost_pair(6, 3, 7)
+    assert (int(ex["synth_dgx1_lat_optimal_cost"][0]), Fraction(ex["synth_dgx1_lat_optimal_cost"][1])) == cost.cost_pair(2, 2, 3)
+    # per-step form sums to the whole
+    assert cost.running_time(6, [1, 2, 4], 1e6, 3e-6, 1e-9) == pytest.approx(3 * 3e-6 + (7 / 6) * 1e6 * 1e-9)
+    assert cost.dominates(cost.cost_pair(6, 3, 7), cost.cost_pair(6, 7, 7))
+
+
+def test_table_rows_respect_the_bounds_and_the_composition_identity():
+    for table, topo in ((T4, tp.dgx1()), (T5, tp.ring(8))):
+        ag = [(C, S, R) for (n, C, S, R, a, b, o) in table if n == "allgather"]
+        ar = [(C, S, R) for (n, C, S, R, a, b, o) in table if n == "allreduce"]
+        for (C, S, R) in ag:
+            assert S >= tp.diameter(topo)
+            assert Fraction(R, C) >= tp.allgather_bandwidth_bound(topo)
+        # every Allreduce row is (P*C, 2S, 2R) of an Allgather row, in the same order
+        assert ar == [(8 * C, 2 * S, 2 * R) for (C, S, R) in ag]
+        for (n, C, S, R, a, b, o) in table:
+            if n == "allgather" and o in ("latency", "both"):
+                assert S == tp.diameter(topo)
+            if n == "allgather" and o in ("bandwidth", "both"):
+                assert Fraction(R, C) == tp.allgather_bandwidth_bound(topo)
+
+
+@pytest.mark.parametrize("P,expect", [(3, 1), (4, 2), (5, 2), (6, 3)])
+def test_exhaustive_search_confirms_minimal_steps_on_rings(P, expect):
+    topo, ag = tp.ring(P), col.allgather(P, 1)
+    S, witness = search.min_steps(topo, ag)
+    assert S == expect == P // 2
+    assert validate(topo, ag, witness).ok
+    if expect > 1:
+        assert search.search(topo, ag, [1] * (expect - 1)) is None
+    assert gen.greedy_bfs(topo, ag).num_steps == S        # greedy reaches the minimum here
+
+
+def test_exhaustive_search_on_hand_made_graphs():
+    # a directed 3-cycle: the chunk of node n needs two hops to reach n-1
+    cyc = tp.point_to_point(3, {(0, 1): 1, (1, 2): 1, (2, 0): 1})
+    S, w = search.min_steps(cyc, col.allgather(3, 1))
+    assert S == 2 and validate(cyc, col.allgather(3, 1), w).ok
+    # a path 0-1-2: node 1 is a bottleneck only in steps, diameter 2
+    path = tp.point_to_point(3, {(0, 1): 1, (1, 0): 1, (1, 2): 1, (2, 1): 1})
+    S, w = search.min_steps(path, col.allgather(3, 1))
+    assert S == 2 == tp.diameter(path)
+    # a star with unit links into the hub: leaves' chunks reach the other leaves through the hub,
+    # and the hub can forward only one chunk per leaf link per step -> 1 + 2 steps for 3 leaves
+    star = tp.point_to_point(4, {(0, i): 1 for i in (1, 2, 3)} | {(i, 0): 1 for i in (1, 2, 3)})
+    S, w = search.min_steps(star, col.allgather(4, 1))
+    assert S == 3
+    assert S >= Fraction(3, 1) == tp.allgather_bandwidth_bound(star)
+    g = gen.greedy_bfs(star, col.allgather(4, 1))
+    assert validate(star, col.allgather(4, 1), g).ok and g.num_steps >= S
+    # with two rounds in the second step the recursive-doubling class (S=2, R=3) is feasible on the 4-ring
+    assert search.search(tp.ring(4), col.allgather(4, 1), [1]) is None
+    assert search.search(tp.ring(4), col.allgather(4, 1), [1, 2]) is not None
+    # broadcast on the 4-ring from node 0 takes the eccentricity of node 0
+    S, w = search.min_steps(tp.ring(4), col.broadcast(4, 1, 0))
+    assert S == 2
+
+
+def test_inversion_and_composition():
+    for topo, C in ((tp.hcm8(), 1), (tp.ring(4), 1), (tp.torus2d(4, 4), 1), (tp.dgx1(), 2)):
+        P = topo.num_nodes
+        ag = col.allgather(P, C)
+        s = gen.greedy_bfs(topo, ag)
+        rs, rsc = gen.reducescatter_from(s, ag)
+        assert validate(topo.reversed(), rsc, rs).ok
+        assert (rs.sends[:, 4] == REDUCE).all()
+        assert rs.rounds == list(reversed(s.rounds))
+        # inverse of the inverse is the original set of sends
+        back = {(c, m, n, s.num_steps - 1 - st) for (c, n, m, st, op) in rs.sends.tolist()}
+        assert back == {(c, n, m, st) for (c, n, m, st, op) in s.sends.tolist()}
+        ar, arc = gen.compose_allreduce(s, ag)
+        assert validate(topo, arc, ar).ok
+        assert ar.csr(arc.num_chunks) == (P * C, 2 * s.num_steps, 2 * s.num_rounds)
+        # sorted by (step, dst, chunk, src) inside the reducing half
+        half = ar.sends[: rs.sends.shape[0]].tolist()
+        assert half == sorted(half, key=lambda t: (t[3], t[2], t[0], t[1]))
+
+
+def test_inversion_refuses_redundant_receives():
+    ag = col.allgather(3, 1)
+    sends = [(n, n, (n + 1) % 3, 0, COPY) for n in range(3)] + [(n, n, (n - 1) % 3, 0, COPY) for n in range(3)]
+    dup = Schedule([1, 1], np.array(sends + [(0, 0, 1, 1, COPY)], dtype=np.int32))
+    with pytest.raises(gen.GenerationError):
+        gen.invert(dup, ag)
+
+
+def test_inversion_on_an_asymmetric_topology_uses_reversed_links():
+    # directed 3-cycle broadcast from 0: 0->1->2; the reduce runs 2->1->0, which only exists on the reversed graph
+    cyc = tp.point_to_point(3, {(0, 1): 1, (1, 2): 1, (2, 0): 1})
+    bc = col.broadcast(3, 1, 0)
+    s = gen.greedy_bfs(cyc, bc)
+    assert validate(cyc, bc, s).ok and s.num_steps == 2
+    red = gen.invert(s, bc)
+    rc = col.reduce(3, 1, 0)
+    assert validate(cyc.reversed(), rc, red).ok
+    assert validate(cyc, rc, red).verdict is Verdict.SEND_NO_LINK
