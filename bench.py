@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the schedule executor on one MI355X.
+
+A step is one sccl_execute of the whole schedule (all S steps of sends) on P virtual ranks'
+buffers resident in HBM.  Default workload: Allreduce fp32, 8 ranks x 256 MiB on the 8-node
+graph (configuration 3).  Every step is timed with HIP events recorded on the stream the kernel
+is launched on; the in-place buffers are restored from a pristine device copy between steps,
+outside the timed windows.
+
+Prints ONE JSON line on stdout.  `--report` additionally times the other configurations and
+writes a table under gpurun_out/.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def make_inputs(wl, sf, device):
+    """Pristine device buffers for a workload (seeded, generated on the device; bit-identical to the host recipe
+    for the integer-derived distributions)."""
+    import torch
+    from paper_2008_08708_amd import inputs
+    n_elems = wl.bytes_per_rank // wl.elem_bytes
+    epc = n_elems // sf.num_chunks
+    bufs = []
+    for n in range(sf.num_nodes):
+        b = inputs.torch_rank_buffer(wl.dist, wl.dtype, wl.seed, n, n_elems, device)
+        if wl.poison_non_owned:
+            view = b.view(torch.int32 if wl.elem_bytes == 4 else torch.int16)
+            pat = inputs.POISON_U32 if wl.elem_bytes == 4 else inputs.POISON_U16
+            for c in range(sf.num_chunks):
+                if not sf.pre[c, n]:
+                    view[c * epc:(c + 1) * epc] = pat
+        bufs.append(b)
+    return bufs, epc
+
+
+def time_workload(wl, steps, warmup, options=None, keep=False):
+    """Returns dict with per-step kernel times (ms) measured by events on the launch stream."""
+    import torch
+    from paper_2008_08708_amd import schedule_file, sccl
+    dev = torch.device("cuda:0")
+    sf = schedule_file.load(wl.schedule)
+    pristine, epc = make_inputs(wl, sf, dev)
+    work = [torch.empty_like(b) for b in pristine]
+    plan = sccl.sccl_plan_create(*sf.descriptions(wl.dtype, epc), options=options)
+    stats = sccl.sccl_plan_stats(plan)
+    stream = torch.cuda.current_stream()
+
+    def restore():
+        for w, p in zip(work, pristine):
+            w.copy_(p)
+
+    for _ in range(warmup):
+        restore()
+        sccl.sccl_execute(plan, work, stream)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in evs:
+        restore()                      # outside the timed window
+        a.record(stream)
+        sccl.sccl_execute(plan, work, stream)
+        b.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = [a.elapsed_time(b) for a, b in evs]
+    out = {"ms": ms, "wall_s": wall, "stats": stats, "sf": sf, "epc": epc}
+    if keep:
+        out.update({"pristine": pristine, "work": work, "plan": plan})
+    else:
+        sccl.sccl_plan_destroy(plan)
+    return out
+
+
+def copy_ceiling(nbytes, reps=10):
+    """GB/s (read + write) of a plain 16-byte-per-lane copy kernel over nbytes."""
+    import torch
+    from paper_2008_08708_amd import sccl
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+    dst = torch.empty_like(src)
+    stream = torch.cuda.current_stream()
+    for _ in range(2):
+        sccl.sccl_copy_kernel(dst, src, nbytes, stream)
+    evs = []
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        sccl.sccl_copy_kernel(dst, src, nbytes, stream)
+        b.record(stream)
+        evs.append((a, b))
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in evs)
+    return 2.0 * nbytes / (ms[len(ms) // 2] * 1e-3) / 1e9
+
+
+def cpu_baseline(run, wl):
+    """The oracle, as it stands, on the host cores: the full workload, same plan, same input bits.
+    Also compares the GPU's result with it, bit for bit, on the full buffers."""
+    import numpy as np
+    import torch
+    from oracle import executor, schedule as osched
+    from paper_2008_08708_amd import sccl
+    sf, epc = run["sf"], run["epc"]
+    sched = osched.Schedule(sf.rounds, sf.sends)
+    threads = min(16, os.cpu_count() or 1, executor.max_threads())
+    host_in = [p.cpu().numpy() for p in run["pristine"]]
+    times = []
+    host = None
+    for rep in range(3):
+        host = [h.copy() for h in host_in]
+        t0 = time.perf_counter()
+        executor.execute(wl.dtype, sf.num_chunks, epc, sched, host, threads=threads)
+        times.append(time.perf_counter() - t0)
+    # the GPU's result on the same inputs
+    for w, p in zip(run["work"], run["pristine"]):
+        w.copy_(p)
+    sccl.sccl_execute(run["plan"], run["work"])
+    torch.cuda.synchronize()
+    same = True
+    for n, w in enumerate(run["work"]):
+        g = w.cpu().numpy()
+        u = np.uint32 if g.dtype.itemsize == 4 else np.uint16
+        if not (g.view(u) == host[n].view(u)).all():
+            same = False
+    med = sorted(times)[1]
+    return {"value": run["stats"]["bytes_min"] / med / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"the full workload ({run['stats']['bytes_min'] / 2**30:.2f} GiB algorithmic), median of 3 runs, "
+                      f"OpenMP over the element range"}, same
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--block-threads", type=int, default=0)
+    ap.add_argument("--vectors-per-thread", type=int, default=0)
+    ap.add_argument("--max-workgroups", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--report", action="store_true", help="also time the other configurations; table under gpurun_out/")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build executes P virtual ranks on ONE GPU; --gpus N with N > 1 is not supported "
+              "(no inter-GPU path exists in this repository)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2008_08708_amd import sccl, workloads
+    sccl.lib()                                    # fails loudly when the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    options = {k: v for k, v in (("block_threads", args.block_threads), ("vectors_per_thread", args.vectors_per_thread),
+                                 ("max_workgroups", args.max_workgroups)) if v}
+    wl = workloads.WORKLOADS[args.workload]
+    run = time_workload(wl, args.steps, args.warmup, options or None, keep=True)
+    st = run["stats"]
+    ms = run["ms"]
+    mean_ms = sum(ms) / len(ms)
+    gbs = st["bytes_min"] / (mean_ms * 1e-3) / 1e9
+    line = {
+        "metric": "effective HBM GB/s (% peak) executing Allreduce, 8 ranks x 256 MiB fp32"
+                  if args.workload == "cfg3" else f"effective HBM GB/s executing {wl.schedule}",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(mean_ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"f32": "f32", "f16": "f16 (f32 accumulate)", "i32": "i32"}[wl.dtype], "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.schedule}, P={st['num_nodes']} virtual ranks x "
+                               f"{wl.bytes_per_rank >> 20} MiB {wl.dtype}, G={st['num_global_chunks']} chunks, "
+                               f"S={st['num_steps']} steps, {st['num_sends']} sends",
+                   "bytes_min": st["bytes_min"], "bytes_unfused": st["bytes_unfused"],
+                   "grid": st["grid_workgroups"], "block_threads": st["block_threads"],
+                   "vectors_per_thread": st["vectors_per_thread"]},
+        "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "ms_min": round(min(ms), 4), "ms_median": round(sorted(ms)[len(ms) // 2], 4),
+        "wall_ms_per_step_incl_restore": round(run["wall_s"] * 1e3 / args.steps, 4),
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "sccl_exec_kernel (one launch = the whole schedule)",
+                     "algorithmic_bytes_per_launch": st["bytes_min"]},
+    }
+    try:
+        line["copy_kernel_ceiling_gbs"] = round(copy_ceiling(1 << 30), 1)
+    except Exception as e:                        # measurement aid only
+        line["copy_kernel_ceiling_gbs"] = None
+        print(f"copy ceiling failed: {e}", file=sys.stderr)
+    if not args.no_cpu_baseline:
+        base, same = cpu_baseline(run, wl)
+        line["cpu_baseline"] = base
+        line["parity_full_buffers_bitwise"] = bool(same)
+    sccl.sccl_plan_destroy(run["plan"])
+    del run
+    torch.cuda.empty_cache()
+
+    if args.report:
+        rows = []
+        names = [("cfg1", workloads.WORKLOADS["cfg1"]), ("cfg2", workloads.WORKLOADS["cfg2"]),
+                 ("cfg3", workloads.WORKLOADS["cfg3"]), ("cfg4", workloads.WORKLOADS["cfg4"]),
+                 ("cfg4b", workloads.WORKLOADS["cfg4b"])]
+        for coll in ("allgather", "allreduce"):
+            for size in workloads.sweep_sizes():
+                names.append((f"cfg5 {coll} {size}", workloads.sweep_workload(coll, size)))
+        for label, w in names:
+            steps = 5 if w.bytes_per_rank >= (1 << 30) else 20
+            r = time_workload(w, steps, 3)
+            m = sorted(r["ms"])
+            med = m[len(m) // 2]
+            s = r["stats"]
+            rows.append((label, s["num_nodes"], w.bytes_per_rank, s["chunk_bytes"], s["num_steps"], s["bytes_min"],
+                         med * 1e3, m[0] * 1e3, s["bytes_min"] / (med * 1e-3) / 1e9, s["block_threads"],
+                         s["vectors_per_thread"], s["grid_workgroups"]))
+            print(f"[report] {label}: {med * 1e3:.1f} us median, {rows[-1][8]:.1f} GB/s", file=sys.stderr, flush=True)
+            del r
+            torch.cuda.empty_cache()
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_report.md"), "w") as f:
+            f.write("| workload | P | bytes/rank | chunk bytes | S | bytes_min | median us | min us | effective GB/s | % of 8 TB/s | block | vec/lane | grid |\n")
+            f.write("|---|---|---|---|---|---|---|---|---|---|---|---|---|\n")
+            for r in rows:
+                f.write(f"| {r[0]} | {r[1]} | {r[2]} | {r[3]} | {r[4]} | {r[5]} | {r[6]:.1f} | {r[7]:.1f} | {r[8]:.1f} | "
+                        f"{100 * r[8] / HBM_PEAK_GBS:.1f} | {r[9]} | {r[10]} | {r[11]} |\n")
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,198 @@
+/*
+ * sccl.h -- C ABI of the MI355X schedule executor.
+ *
+ * The library executes a k-chunk, S-step collective schedule in the sense of
+ * "Synthesizing Optimal Collective Algorithms" (SCCL) for P *virtual* ranks
+ * whose buffers all live in the memory of ONE GPU.  It does not synthesize
+ * schedules; it validates and runs them.
+ *
+ * Vocabulary (paper, section 3.2-3.3):
+ *   P        number of nodes (ranks)
+ *   G        global number of chunks; every rank buffer is one contiguous
+ *            array of G chunks and chunk c sits at element offset
+ *            c * elems_per_chunk in EVERY rank's buffer (global chunk
+ *            numbering, section 3.2.2).  Collectives run in place.
+ *   B        bandwidth relation: pairs (L, b), L a set of directed node
+ *            pairs, b the number of chunks that may cross L per round
+ *            (section 3.2.1)
+ *   pre/post relations over (chunk, node) (Tables 1 and 2)
+ *   (Q, T)   the schedule: Q = r_0..r_{S-1} rounds per step, T a set of sends
+ *            (c, n, n', s) (section 3.3).  Steps are numbered from 0.
+ *
+ * All pointers in the structs below are HOST pointers, read during the call
+ * and never retained.  rank_buffers[] entries are DEVICE pointers.
+ * Functions return a status and never throw, abort or print.
+ */
+#ifndef SCCL_H
+#define SCCL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SCCL_MAX_RANKS 64          /* P may not exceed this */
+
+typedef enum {
+    SCCL_OK = 0,
+    SCCL_ERR_INVALID_ARG = 1,      /* null pointer, index out of range, r_s < 1, unknown op/dtype, P > SCCL_MAX_RANKS,
+                                      REDUCE send in a non-combining collective */
+    SCCL_ERR_TOPOLOGY = 2,         /* malformed bandwidth relation (edge out of range, negative b, self loop) */
+    SCCL_ERR_SEND_NO_SOURCE = 3,   /* a send reads (c, n) that is not in V_s (section 3.3), or that was consumed */
+    SCCL_ERR_SEND_NO_LINK = 4,     /* (n, n') is not a usable link: not in E of section 3.4 */
+    SCCL_ERR_BANDWIDTH = 5,        /* some (L, b) sees more than b * r_s sends in step s (section 3.3) */
+    SCCL_ERR_POSTCONDITION = 6,    /* post not reached after S steps */
+    SCCL_ERR_HAZARD = 7,           /* a step reads and writes one (c, n), writes it twice, or counts a rank twice */
+    SCCL_ERR_ALIGNMENT = 8,        /* a rank buffer is not 16-byte aligned */
+    SCCL_ERR_OVERLAP = 9,          /* two rank buffers overlap */
+    SCCL_ERR_NOMEM = 10,
+    SCCL_ERR_DEVICE = 11           /* a HIP call failed, or execute on a host-only plan */
+} sccl_status_t;
+
+typedef enum {
+    SCCL_I32 = 0,                  /* wrapping 32-bit sum */
+    SCCL_F32 = 1,                  /* IEEE binary32 add, round to nearest even */
+    SCCL_F16 = 2                   /* binary16 in memory; widened exactly to binary32, summed in binary32 and
+                                      rounded to nearest even ONCE per reduce group per step */
+} sccl_dtype_t;
+
+typedef enum { SCCL_COPY = 0, SCCL_REDUCE_SUM = 1 } sccl_sendop_t;
+
+/* One directed node pair. */
+typedef struct { int32_t src, dst; } sccl_edge_t;
+
+/* One element (L, b) of the bandwidth relation B (section 3.2.1): at most
+ * chunks_per_round * r_s sends of step s may use the edges listed.  A pair is a
+ * usable link iff at least one entry lists it and every entry that lists it
+ * has chunks_per_round > 0. */
+typedef struct {
+    const sccl_edge_t* edges;
+    int32_t num_edges;
+    int32_t chunks_per_round;
+} sccl_bw_t;
+
+typedef struct {
+    int32_t num_nodes;             /* P */
+    const sccl_bw_t* bw;
+    int32_t num_bw;
+} sccl_topology_t;
+
+/* A collective as a (pre, post) pair over (chunk, node), Table 2 of the paper.
+ * pre and post are G x P row-major arrays of 0/1 bytes: pre[c*P + n] != 0 iff
+ * (c, n) is in the relation.
+ * combining == 0: chunks are only copied; pre says where chunk c is at the
+ *   start, post where it must be at the end.  Regions outside pre are
+ *   undefined inputs and are never read.
+ * combining == 1 (section 3.5): pre says which ranks hold a *version* of
+ *   chunk c, post where the sum over all P ranks' versions must be at the end
+ *   (Reducescatter: pre All, post Scattered; Allreduce: pre All, post All). */
+typedef struct {
+    int32_t num_global_chunks;     /* G */
+    const uint8_t* pre;
+    const uint8_t* post;
+    int32_t combining;
+    sccl_dtype_t dtype;
+    int64_t elems_per_chunk;       /* >= 0; chunk bytes = elems_per_chunk * sizeof(dtype) */
+} sccl_collective_t;
+
+/* One send (c, n, n', s) of section 3.3 plus, for combining collectives, what
+ * the receiver does with it (section 4, first paragraph): SCCL_COPY replaces
+ * the destination's chunk, SCCL_REDUCE_SUM adds the source's version to it. */
+typedef struct { int32_t chunk, src, dst, step; int32_t op; } sccl_send_t;
+
+/* The candidate solution (Q, T).  The ORDER of `sends` matters: all
+ * SCCL_REDUCE_SUM sends of one step into the same (chunk, dst) form one group
+ * and are added left to right in array order, starting from the
+ * destination's own value. */
+typedef struct {
+    int32_t num_steps;             /* S */
+    const int32_t* rounds;         /* Q: r_0 .. r_{S-1}, each >= 1 */
+    const sccl_send_t* sends;
+    int64_t num_sends;
+} sccl_schedule_t;
+
+/* Options of sccl_plan_create_ex; zero-initialise for the defaults. */
+#define SCCL_PLAN_HOST_ONLY 1u     /* validate and compile only: touches no device; the plan cannot be executed */
+typedef struct {
+    uint32_t flags;
+    int32_t block_threads;         /* 0 = choose from the chunk size; else 64, 128 or 256 */
+    int32_t vectors_per_thread;    /* 0 = choose; else 1, 2 or 4: vectors each lane moves per operand */
+    int32_t max_workgroups;        /* 0 = choose from the device's CU count; else an upper bound on the grid */
+    int32_t cache_hints;           /* 0 = default (on); 1 = off; 2 = on: streaming loads/stores for data touched once */
+} sccl_options_t;
+
+typedef struct {
+    int32_t num_nodes, num_global_chunks;
+    int32_t num_steps;             /* S */
+    int32_t num_rounds;            /* R = sum of Q */
+    int32_t k;                     /* R - S: the schedule is k-synchronous (section 3.1) */
+    int64_t num_sends;
+    int64_t num_copy_groups;       /* (step, chunk, src) groups */
+    int64_t num_reduce_groups;     /* (step, chunk, dst) groups */
+    int32_t max_fan_in, max_fan_out;
+    int64_t chunk_bytes;
+    int64_t bytes_per_rank;        /* G * chunk_bytes */
+    int64_t bytes_min;             /* sum over copy groups of (1 + k) chunks and over reduce groups of (k + 2) chunks */
+    int64_t bytes_unfused;         /* 2 chunks per COPY send + 3 per REDUCE send */
+    /* launch shape chosen for the kernel */
+    int32_t vector_bytes;          /* 16, 8, 4 or 2: widest access that divides the chunk size */
+    int32_t block_threads, vectors_per_thread;
+    int64_t num_work_items;        /* G * tiles per chunk */
+    int32_t grid_workgroups;       /* 0 for a host-only plan */
+} sccl_stats_t;
+
+typedef struct sccl_plan sccl_plan_t;
+
+/*
+ * Validate (Q, T) against the topology and the collective (section 3.3's run
+ * and bandwidth constraint; for combining collectives the contribution-set
+ * rules documented at SCCL_ERR_HAZARD) and compile it into a device step
+ * table on the current HIP device.  Everything passed in is deep-copied; the
+ * caller may free its arrays on return.  On error *out_plan is NULL.
+ * The plan owns its device memory until sccl_plan_destroy.
+ */
+sccl_status_t sccl_plan_create(const sccl_topology_t* topology, const sccl_collective_t* collective,
+                               const sccl_schedule_t* schedule, sccl_plan_t** out_plan);
+
+/* As above with explicit options (may be NULL). */
+sccl_status_t sccl_plan_create_ex(const sccl_topology_t* topology, const sccl_collective_t* collective,
+                                  const sccl_schedule_t* schedule, const sccl_options_t* options,
+                                  sccl_plan_t** out_plan);
+
+/*
+ * Execute the plan in place: all S steps of sends (section 3.3; lowered as one
+ * kernel as in section 4, "single kernel") on the P device buffers
+ * rank_buffers[0..P-1], each G * elems_per_chunk elements, 16-byte aligned and
+ * pairwise disjoint (checked: SCCL_ERR_ALIGNMENT / SCCL_ERR_OVERLAP).
+ * `stream` is a hipStream_t (NULL = the default stream).  The call enqueues
+ * one kernel and returns; it does not synchronise and does not allocate.  The
+ * pointer array is read on the host during the call.  Nothing is launched
+ * when the status is not SCCL_OK.  A plan is immutable: concurrent calls with
+ * one plan are allowed as long as their buffers differ.
+ */
+sccl_status_t sccl_execute(const sccl_plan_t* plan, void* const* rank_buffers, void* stream);
+
+/* S, R, k, group counts, algorithmic byte counts and the launch shape. */
+sccl_status_t sccl_plan_stats(const sccl_plan_t* plan, sccl_stats_t* out_stats);
+
+/* Frees host and device memory of the plan; NULL is allowed.  The caller
+ * makes sure no execute of this plan is still running. */
+void sccl_plan_destroy(sccl_plan_t* plan);
+
+const char* sccl_status_string(sccl_status_t status);
+
+/*
+ * Measurement aid, not part of the method: a plain 16-byte-per-lane copy
+ * kernel dst[i] = src[i] over `bytes` bytes (a multiple of 16, both pointers
+ * 16-byte aligned device memory), enqueued on `stream`.  Used to measure the
+ * achievable copy bandwidth on the same buffers and to calibrate hardware
+ * byte counters against a known traffic volume.
+ */
+sccl_status_t sccl_copy_kernel(void* dst, const void* src, size_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCCL_H */

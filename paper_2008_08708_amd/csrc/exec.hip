@@ -1,0 +1,401 @@
+// Device side of the library: the gfx950 executor kernel, plan upload and the C entry points.
+//
+// How a schedule is executed (paper, section 4: all steps fused into ONE kernel, a chunk
+// being usable as soon as the send that produces it is done -- there with a flag per
+// chunk and connection, no global barrier between steps):
+//
+//   * Every rank buffer holds chunk c at the same offset, so the sends of different
+//     chunks touch disjoint memory, and sends of one chunk act element by element.  The
+//     only order the schedule imposes is therefore, per chunk and per element, the
+//     order of that chunk's sends by step.
+//   * The element range of a chunk is cut into tiles; a work item is (chunk, tile).  A
+//     workgroup takes a work item and walks the chunk's whole op list, step by step.
+//     Lane t of the workgroup touches the SAME element positions in every op, so every
+//     value a lane reads in step s+1 was written by that same lane in step s: the
+//     inter-step dependency is plain program order of one thread.  No flags, no
+//     barrier, no cross-workgroup visibility is needed, and the result is bit-identical
+//     to the synchronous execution because each element sees the same operations in
+//     the same order.
+//   * One op = one copy group (load once, store to every destination) or one reduce
+//     group (load destination and all sources, add left to right in fp32 / wrapping
+//     int32, store once).  All loads of an op are issued before the first use.
+//   * Values travel through memory between steps (L2 / memory-side cache absorb most
+//     of the re-reads because a lane re-reads what it just wrote); nothing is kept in
+//     registers across ops.
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstring>
+#include <new>
+
+#include "plan.hpp"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+template <int W> struct VecOf;
+template <> struct VecOf<16> { typedef u32x4 type; };
+template <> struct VecOf<8>  { typedef u32x2 type; };
+template <> struct VecOf<4>  { typedef uint32_t type; };
+template <> struct VecOf<2>  { typedef uint16_t type; };
+
+// The step table is written once at plan creation and never by a kernel: reading it through
+// the constant address space lets the compiler use scalar loads (one fetch per wavefront,
+// not ordered against the data loads' counter).
+typedef const int32_t __attribute__((address_space(4)))* table_ptr;
+
+struct ExecArgs {
+    const int32_t* prog;
+    const int32_t* chunk_off;
+    int64_t vecs_per_chunk;
+    int64_t num_items;
+    int32_t tiles_per_chunk;
+    int32_t pad;
+    char* bufs[SCCL_MAX_RANKS];
+};
+
+// ---- memory access.  The plan marks operands whose data is not reused (OPERAND_STREAM); the
+// kernel does not act on the mark yet: a run-time choice between a plain and a non-temporal
+// access of the same address is folded into one plain access by the compiler.
+template <typename V>
+__device__ __forceinline__ V load_vec(const char* p) {
+    return *reinterpret_cast<const V*>(p);
+}
+template <typename V>
+__device__ __forceinline__ void store_vec(char* p, V v) {
+    *reinterpret_cast<V*>(p) = v;
+}
+
+// ---- accumulators: how one vector of W bytes is widened, summed and narrowed per dtype
+template <int DT, int W> struct Acc;
+
+template <int W> struct Acc<SCCL_I32, W> {           // wrapping sum modulo 2^32
+    static constexpr int N = W / 4;
+    uint32_t a[N];
+    template <typename V> __device__ __forceinline__ void init(V v) { __builtin_memcpy(a, &v, W); }
+    template <typename V> __device__ __forceinline__ void add(V v) {
+        uint32_t x[N]; __builtin_memcpy(x, &v, W);
+#pragma unroll
+        for (int i = 0; i < N; i++) a[i] += x[i];
+    }
+    template <typename V> __device__ __forceinline__ V done() { V v; __builtin_memcpy(&v, a, W); return v; }
+};
+
+template <int W> struct Acc<SCCL_F32, W> {           // binary32 add, round to nearest even
+    static constexpr int N = W / 4;
+    float a[N];
+    template <typename V> __device__ __forceinline__ void init(V v) { __builtin_memcpy(a, &v, W); }
+    template <typename V> __device__ __forceinline__ void add(V v) {
+        float x[N]; __builtin_memcpy(x, &v, W);
+#pragma unroll
+        for (int i = 0; i < N; i++) a[i] = a[i] + x[i];
+    }
+    template <typename V> __device__ __forceinline__ V done() { V v; __builtin_memcpy(&v, a, W); return v; }
+};
+
+template <int W> struct Acc<SCCL_F16, W> {           // binary16 in memory, binary32 sum, one RNE narrowing
+    static constexpr int N = W / 2;
+    float a[N];
+    template <typename V> __device__ __forceinline__ void init(V v) {
+        _Float16 h[N]; __builtin_memcpy(h, &v, W);
+#pragma unroll
+        for (int i = 0; i < N; i++) a[i] = (float)h[i];
+    }
+    template <typename V> __device__ __forceinline__ void add(V v) {
+        _Float16 h[N]; __builtin_memcpy(h, &v, W);
+#pragma unroll
+        for (int i = 0; i < N; i++) a[i] = a[i] + (float)h[i];
+    }
+    template <typename V> __device__ __forceinline__ V done() {
+        _Float16 h[N];
+#pragma unroll
+        for (int i = 0; i < N; i++) h[i] = (_Float16)a[i];     // default rounding mode: nearest even
+        V v; __builtin_memcpy(&v, h, W); return v;
+    }
+};
+
+// NS sources of a reduce group (NS is a compile-time batch size): issue every load, then add in
+// order.  In the FIRST batch the accumulators start from the destination's value d0, whose load
+// was issued just before this batch's loads, so all of them are in flight together.
+template <int DT, int W, int U, int NS, bool FULL, bool FIRST>
+__device__ __forceinline__ void reduce_batch(Acc<DT, W> (&acc)[U], const typename VecOf<W>::type (&d0)[U],
+                                             const ExecArgs& a, table_ptr srcs,
+                                             int64_t off, int64_t stride, const bool (&ok)[U]) {
+    typedef typename VecOf<W>::type V;
+    V x[NS][U];
+#pragma unroll
+    for (int j = 0; j < NS; j++) {
+        const int32_t w = srcs[j];
+        const char* p = a.bufs[w & OPERAND_RANK_MASK] + off;
+#pragma unroll
+        for (int u = 0; u < U; u++)
+            if (FULL || ok[u]) x[j][u] = load_vec<V>(p + u * stride);
+    }
+    if (FIRST) {
+#pragma unroll
+        for (int u = 0; u < U; u++)
+            if (FULL || ok[u]) acc[u].init(d0[u]);
+    }
+#pragma unroll
+    for (int j = 0; j < NS; j++)
+#pragma unroll
+        for (int u = 0; u < U; u++)
+            if (FULL || ok[u]) acc[u].add(x[j][u]);
+}
+
+template <int DT, int W, int U, bool FULL, bool FIRST>
+__device__ __forceinline__ void reduce_some(int32_t n, Acc<DT, W> (&acc)[U], const typename VecOf<W>::type (&d0)[U],
+                                            const ExecArgs& a, table_ptr srcs,
+                                            int64_t off, int64_t stride, const bool (&ok)[U]) {
+    switch (n) {
+        case 4:  reduce_batch<DT, W, U, 4, FULL, FIRST>(acc, d0, a, srcs, off, stride, ok); break;
+        case 3:  reduce_batch<DT, W, U, 3, FULL, FIRST>(acc, d0, a, srcs, off, stride, ok); break;
+        case 2:  reduce_batch<DT, W, U, 2, FULL, FIRST>(acc, d0, a, srcs, off, stride, ok); break;
+        default: reduce_batch<DT, W, U, 1, FULL, FIRST>(acc, d0, a, srcs, off, stride, ok); break;
+    }
+}
+
+template <int DT, int W, int U, bool FULL>
+__device__ __forceinline__ void run_ops(const ExecArgs& a, table_ptr op, table_ptr end,
+                                        int64_t off, int64_t stride, const bool (&ok)[U]) {
+    typedef typename VecOf<W>::type V;
+    while (op < end) {
+        const int32_t hdr = op[0];
+        const int32_t k = hdr >> 8;
+        if ((hdr & OP_KIND_REDUCE) == 0) {
+            // copy group: one read, k writes
+            const int32_t ws = op[1];
+            const char* ps = a.bufs[ws & OPERAND_RANK_MASK] + off;
+            V x[U];
+#pragma unroll
+            for (int u = 0; u < U; u++)
+                if (FULL || ok[u]) x[u] = load_vec<V>(ps + u * stride);
+            for (int32_t d = 0; d < k; d++) {
+                const int32_t wd = op[2 + d];
+                char* pd = a.bufs[wd & OPERAND_RANK_MASK] + off;
+#pragma unroll
+                for (int u = 0; u < U; u++)
+                    if (FULL || ok[u]) store_vec<V>(pd + u * stride, x[u]);
+            }
+        } else {
+            // reduce group: destination first, then the k sources in schedule order
+            const int32_t wd = op[1];
+            char* pd = a.bufs[wd & OPERAND_RANK_MASK] + off;
+            Acc<DT, W> acc[U];
+            V d0[U];
+#pragma unroll
+            for (int u = 0; u < U; u++)
+                if (FULL || ok[u]) d0[u] = load_vec<V>(pd + u * stride);
+            table_ptr srcs = op + 2;
+            int32_t left = k;                                  // k >= 1
+            int32_t n = left < 4 ? left : 4;
+            reduce_some<DT, W, U, FULL, true>(n, acc, d0, a, srcs, off, stride, ok);
+            srcs += n; left -= n;
+            while (left > 0) {                                 // fan-in above 4: further batches, still in order
+                n = left < 4 ? left : 4;
+                reduce_some<DT, W, U, FULL, false>(n, acc, d0, a, srcs, off, stride, ok);
+                srcs += n; left -= n;
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++)
+                if (FULL || ok[u]) store_vec<V>(pd + u * stride, acc[u].template done<V>());
+        }
+        op += 2 + k;
+    }
+}
+
+// Persistent kernel: workgroup b takes work items b, b + grid, ... ; a work item is (chunk, tile).
+template <int DT, int W, int U>
+__global__ void __launch_bounds__(256) sccl_exec_kernel(const ExecArgs a) {
+    const int64_t tile_vecs = (int64_t)blockDim.x * U;
+    const int64_t stride = (int64_t)blockDim.x * W;           // bytes between a lane's consecutive vectors
+    for (int64_t item = blockIdx.x; item < a.num_items; item += gridDim.x) {
+        const int32_t c = (int32_t)(item / a.tiles_per_chunk);
+        const int32_t tile = (int32_t)(item - (int64_t)c * a.tiles_per_chunk);
+        const int64_t v0 = (int64_t)tile * tile_vecs + threadIdx.x;
+        const int64_t off = ((int64_t)c * a.vecs_per_chunk + v0) * W;
+        table_ptr offs = (table_ptr)a.chunk_off;
+        table_ptr op = (table_ptr)a.prog + offs[c];
+        table_ptr end = (table_ptr)a.prog + offs[c + 1];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) ok[u] = v0 + (int64_t)u * blockDim.x < a.vecs_per_chunk;
+        if ((int64_t)(tile + 1) * tile_vecs <= a.vecs_per_chunk)
+            run_ops<DT, W, U, true>(a, op, end, off, stride, ok);
+        else
+            run_ops<DT, W, U, false>(a, op, end, off, stride, ok);
+    }
+}
+
+__global__ void __launch_bounds__(256) copy16_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+typedef void (*kernel_fn)(const ExecArgs);
+
+template <int DT, int W>
+kernel_fn pick_u(int U) {
+    switch (U) {
+        case 1: return sccl_exec_kernel<DT, W, 1>;
+        case 2: return sccl_exec_kernel<DT, W, 2>;
+        default: return sccl_exec_kernel<DT, W, 4>;
+    }
+}
+
+template <int DT>
+kernel_fn pick_w(int W, int U) {
+    switch (W) {
+        case 16: return pick_u<DT, 16>(U);
+        case 8:  return pick_u<DT, 8>(U);
+        default: return pick_u<DT, 4>(U);
+    }
+}
+
+kernel_fn pick_kernel(sccl_dtype_t dt, int W, int U) {
+    switch (dt) {
+        case SCCL_I32: return pick_w<SCCL_I32>(W, U);
+        case SCCL_F32: return pick_w<SCCL_F32>(W, U);
+        default:
+            if (W == 2) return pick_u<SCCL_F16, 2>(U);
+            return pick_w<SCCL_F16>(W, U);
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+sccl_status_t sccl_plan_create_ex(const sccl_topology_t* topology, const sccl_collective_t* collective,
+                                  const sccl_schedule_t* schedule, const sccl_options_t* options,
+                                  sccl_plan_t** out_plan) {
+    if (!out_plan) return SCCL_ERR_INVALID_ARG;
+    *out_plan = nullptr;
+    sccl_plan* plan = new (std::nothrow) sccl_plan();
+    if (!plan) return SCCL_ERR_NOMEM;
+    const bool host_only = options && (options->flags & SCCL_PLAN_HOST_ONLY);
+    int num_cus = 256;
+    int dev = -1;
+    sccl_status_t st = SCCL_OK;
+    try {
+        if (!host_only) {
+            hipDeviceProp_t prop;
+            if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+                delete plan;
+                return SCCL_ERR_DEVICE;
+            }
+            num_cus = prop.multiProcessorCount;
+        }
+        st = sccl_compile_host(topology, collective, schedule, options, num_cus, plan);
+    } catch (const std::bad_alloc&) {
+        st = SCCL_ERR_NOMEM;
+    }
+    if (st != SCCL_OK) { delete plan; return st; }
+    if (!host_only) {
+        plan->device = dev;
+        const size_t pb = plan->prog.size() * sizeof(int32_t), ob = plan->chunk_off.size() * sizeof(int32_t);
+        bool good = hipMalloc((void**)&plan->d_prog, pb ? pb : 4) == hipSuccess &&
+                    hipMalloc((void**)&plan->d_chunk_off, ob) == hipSuccess &&
+                    (pb == 0 || hipMemcpy(plan->d_prog, plan->prog.data(), pb, hipMemcpyHostToDevice) == hipSuccess) &&
+                    hipMemcpy(plan->d_chunk_off, plan->chunk_off.data(), ob, hipMemcpyHostToDevice) == hipSuccess;
+        int per_cu = 0;
+        if (good) {
+            kernel_fn fn = pick_kernel(plan->dtype, plan->vector_bytes, plan->vectors_per_thread);
+            good = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)fn, plan->block_threads, 0) == hipSuccess;
+        }
+        if (!good) { sccl_plan_destroy(plan); return SCCL_ERR_DEVICE; }
+        if (per_cu < 1) per_cu = 1;
+        int64_t grid = (int64_t)num_cus * per_cu;
+        if (plan->opts.max_workgroups > 0 && grid > plan->opts.max_workgroups) grid = plan->opts.max_workgroups;
+        if (grid > plan->num_items) grid = plan->num_items;
+        plan->grid = (int32_t)grid;
+        plan->stats.grid_workgroups = plan->grid;
+    }
+    *out_plan = plan;
+    return SCCL_OK;
+}
+
+sccl_status_t sccl_plan_create(const sccl_topology_t* topology, const sccl_collective_t* collective,
+                               const sccl_schedule_t* schedule, sccl_plan_t** out_plan) {
+    return sccl_plan_create_ex(topology, collective, schedule, nullptr, out_plan);
+}
+
+sccl_status_t sccl_execute(const sccl_plan_t* plan, void* const* rank_buffers, void* stream) {
+    if (!plan || !rank_buffers) return SCCL_ERR_INVALID_ARG;
+    if (plan->device < 0) return SCCL_ERR_DEVICE;
+    const int32_t P = plan->P;
+    const uint64_t bytes = (uint64_t)plan->stats.bytes_per_rank;
+    for (int32_t n = 0; n < P; n++) {
+        if (!rank_buffers[n]) return SCCL_ERR_INVALID_ARG;
+        if ((uintptr_t)rank_buffers[n] & 15u) return SCCL_ERR_ALIGNMENT;
+    }
+    for (int32_t n = 0; n < P; n++)
+        for (int32_t m = n + 1; m < P; m++) {
+            const uintptr_t a = (uintptr_t)rank_buffers[n], b = (uintptr_t)rank_buffers[m];
+            if (a == b || (a < b ? a + bytes > b : b + bytes > a)) return SCCL_ERR_OVERLAP;
+        }
+    if (plan->num_items == 0 || plan->prog.empty()) return SCCL_OK;     // nothing to move
+    ExecArgs args;
+    std::memset(&args, 0, sizeof(args));
+    args.prog = plan->d_prog;
+    args.chunk_off = plan->d_chunk_off;
+    args.vecs_per_chunk = plan->vecs_per_chunk;
+    args.num_items = plan->num_items;
+    args.tiles_per_chunk = plan->tiles_per_chunk;
+    for (int32_t n = 0; n < P; n++) args.bufs[n] = (char*)rank_buffers[n];
+    kernel_fn fn = pick_kernel(plan->dtype, plan->vector_bytes, plan->vectors_per_thread);
+    hipLaunchKernelGGL(fn, dim3((unsigned)plan->grid), dim3((unsigned)plan->block_threads), 0, (hipStream_t)stream, args);
+    return hipGetLastError() == hipSuccess ? SCCL_OK : SCCL_ERR_DEVICE;
+}
+
+sccl_status_t sccl_plan_stats(const sccl_plan_t* plan, sccl_stats_t* out_stats) {
+    if (!plan || !out_stats) return SCCL_ERR_INVALID_ARG;
+    *out_stats = plan->stats;
+    return SCCL_OK;
+}
+
+void sccl_plan_destroy(sccl_plan_t* plan) {
+    if (!plan) return;
+    if (plan->d_prog) (void)hipFree(plan->d_prog);
+    if (plan->d_chunk_off) (void)hipFree(plan->d_chunk_off);
+    delete plan;
+}
+
+const char* sccl_status_string(sccl_status_t status) {
+    switch (status) {
+        case SCCL_OK: return "SCCL_OK";
+        case SCCL_ERR_INVALID_ARG: return "SCCL_ERR_INVALID_ARG";
+        case SCCL_ERR_TOPOLOGY: return "SCCL_ERR_TOPOLOGY";
+        case SCCL_ERR_SEND_NO_SOURCE: return "SCCL_ERR_SEND_NO_SOURCE";
+        case SCCL_ERR_SEND_NO_LINK: return "SCCL_ERR_SEND_NO_LINK";
+        case SCCL_ERR_BANDWIDTH: return "SCCL_ERR_BANDWIDTH";
+        case SCCL_ERR_POSTCONDITION: return "SCCL_ERR_POSTCONDITION";
+        case SCCL_ERR_HAZARD: return "SCCL_ERR_HAZARD";
+        case SCCL_ERR_ALIGNMENT: return "SCCL_ERR_ALIGNMENT";
+        case SCCL_ERR_OVERLAP: return "SCCL_ERR_OVERLAP";
+        case SCCL_ERR_NOMEM: return "SCCL_ERR_NOMEM";
+        case SCCL_ERR_DEVICE: return "SCCL_ERR_DEVICE";
+    }
+    return "SCCL_ERR_UNKNOWN";
+}
+
+sccl_status_t sccl_copy_kernel(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src || (bytes & 15u) || ((uintptr_t)dst & 15u) || ((uintptr_t)src & 15u)) return SCCL_ERR_INVALID_ARG;
+    if (bytes == 0) return SCCL_OK;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return SCCL_ERR_DEVICE;
+    const size_t n = bytes / 16;
+    size_t grid = (n + 255) / 256;
+    const size_t cap = (size_t)prop.multiProcessorCount * 8;
+    if (grid > cap) grid = cap;
+    hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream,
+                       (u32x4*)dst, (const u32x4*)src, n);
+    return hipGetLastError() == hipSuccess ? SCCL_OK : SCCL_ERR_DEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,285 @@
+// Host side of the library: validation of a schedule and its compilation into the
+// per-chunk op lists the kernel walks.  No HIP calls in this file.
+//
+// Validation follows the paper's definition of a valid candidate solution
+// (section 3.3): the run V_0 = pre, V_{s+1} = V_s + {(c,n') : (c,n) in V_s and
+// (c,n,n',s) in T}; post must be reached (read as post being a subset of V_S,
+// which is what constraint C2 of section 3.4 states); and for every step s and
+// every (L, b) in B the sends of step s on edges of L number at most b * r_s.
+// Combining collectives (section 3.5) are checked with contribution sets: the
+// set of ranks whose input is summed into the value held at (c, n).
+
+#include "plan.hpp"
+
+#include <algorithm>
+#include <cstring>
+#include <map>
+#include <new>
+#include <utility>
+
+namespace {
+
+struct Group {
+    int32_t kind;                 // 0 copy, 1 reduce
+    int32_t chunk;
+    int32_t anchor;               // copy: source rank; reduce: destination rank
+    std::vector<int32_t> others;  // copy: destinations; reduce: sources (schedule order)
+};
+
+int elem_bytes(sccl_dtype_t d) { return d == SCCL_F16 ? 2 : 4; }
+
+}  // namespace
+
+sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collective_t* coll,
+                                const sccl_schedule_t* sched, const sccl_options_t* opts, int num_cus,
+                                sccl_plan* plan) {
+    if (!topo || !coll || !sched || !plan) return SCCL_ERR_INVALID_ARG;
+    const int32_t P = topo->num_nodes;
+    const int32_t G = coll->num_global_chunks;
+    const int32_t S = sched->num_steps;
+    if (P < 1 || P > SCCL_MAX_RANKS || G < 1 || S < 1) return SCCL_ERR_INVALID_ARG;
+    if (!coll->pre || !coll->post || !sched->rounds) return SCCL_ERR_INVALID_ARG;
+    if (coll->elems_per_chunk < 0) return SCCL_ERR_INVALID_ARG;
+    if (coll->dtype != SCCL_I32 && coll->dtype != SCCL_F32 && coll->dtype != SCCL_F16) return SCCL_ERR_INVALID_ARG;
+    if (sched->num_sends < 0 || (sched->num_sends > 0 && !sched->sends)) return SCCL_ERR_INVALID_ARG;
+    if (topo->num_bw < 0 || (topo->num_bw > 0 && !topo->bw)) return SCCL_ERR_INVALID_ARG;
+    if (opts) {
+        const int32_t bt = opts->block_threads, vt = opts->vectors_per_thread;
+        if (!(bt == 0 || bt == 64 || bt == 128 || bt == 256)) return SCCL_ERR_INVALID_ARG;
+        if (!(vt == 0 || vt == 1 || vt == 2 || vt == 4)) return SCCL_ERR_INVALID_ARG;
+        if (opts->max_workgroups < 0 || opts->cache_hints < 0 || opts->cache_hints > 2) return SCCL_ERR_INVALID_ARG;
+    }
+    int64_t R = 0;
+    for (int32_t s = 0; s < S; s++) {
+        if (sched->rounds[s] < 1) return SCCL_ERR_INVALID_ARG;
+        R += sched->rounds[s];
+    }
+
+    // ---- bandwidth relation: usable links, and for every edge the constraints that cover it
+    std::vector<uint8_t> mentioned((size_t)P * P, 0), blocked((size_t)P * P, 0);
+    std::vector<std::vector<int32_t>> covering((size_t)P * P);
+    for (int32_t i = 0; i < topo->num_bw; i++) {
+        const sccl_bw_t& c = topo->bw[i];
+        if (c.num_edges < 0 || c.chunks_per_round < 0 || (c.num_edges > 0 && !c.edges)) return SCCL_ERR_TOPOLOGY;
+        for (int32_t j = 0; j < c.num_edges; j++) {
+            const int32_t a = c.edges[j].src, b = c.edges[j].dst;
+            if (a < 0 || a >= P || b < 0 || b >= P || a == b) return SCCL_ERR_TOPOLOGY;
+            const size_t e = (size_t)a * P + b;
+            mentioned[e] = 1;
+            if (c.chunks_per_round == 0) blocked[e] = 1;
+            if (covering[e].empty() || covering[e].back() != i) covering[e].push_back(i);
+        }
+    }
+
+    // ---- sends: ranges, ops, links
+    const int64_t N = sched->num_sends;
+    for (int64_t i = 0; i < N; i++) {
+        const sccl_send_t& t = sched->sends[i];
+        if (t.chunk < 0 || t.chunk >= G || t.src < 0 || t.src >= P || t.dst < 0 || t.dst >= P ||
+            t.step < 0 || t.step >= S || t.src == t.dst)
+            return SCCL_ERR_INVALID_ARG;
+        if (t.op != SCCL_COPY && t.op != SCCL_REDUCE_SUM) return SCCL_ERR_INVALID_ARG;
+        if (t.op == SCCL_REDUCE_SUM && !coll->combining) return SCCL_ERR_INVALID_ARG;
+    }
+    for (int64_t i = 0; i < N; i++) {
+        const sccl_send_t& t = sched->sends[i];
+        const size_t e = (size_t)t.src * P + t.dst;
+        if (!mentioned[e] || blocked[e]) return SCCL_ERR_SEND_NO_LINK;
+    }
+
+    // ---- bucket the sends by step, keeping array order inside a step
+    std::vector<int64_t> first((size_t)S + 1, 0);
+    for (int64_t i = 0; i < N; i++) first[(size_t)sched->sends[i].step + 1]++;
+    for (int32_t s = 0; s < S; s++) first[(size_t)s + 1] += first[s];
+    std::vector<int64_t> order((size_t)N);
+    {
+        std::vector<int64_t> fill(first.begin(), first.end() - 1);
+        for (int64_t i = 0; i < N; i++) order[(size_t)fill[sched->sends[i].step]++] = i;
+    }
+
+    // ---- the run, with contribution sets.  held[c*P+n] == 0: chunk not present (or consumed).
+    const uint64_t everyone = (P == 64) ? ~0ull : ((1ull << P) - 1ull);
+    std::vector<uint64_t> held((size_t)G * P, 0);
+    for (int32_t c = 0; c < G; c++)
+        for (int32_t n = 0; n < P; n++)
+            if (coll->pre[(size_t)c * P + n]) held[(size_t)c * P + n] = coll->combining ? (1ull << n) : everyone;
+
+    std::vector<std::vector<Group>> per_chunk((size_t)G);   // op lists in step order
+    std::vector<int64_t> load(topo->num_bw > 0 ? (size_t)topo->num_bw : 1);
+    std::vector<uint8_t> is_read((size_t)G * P, 0), is_written((size_t)G * P, 0);   // 1 copy-written, 2 reduced into
+    int64_t n_copy_groups = 0, n_reduce_groups = 0, chunks_min = 0, chunks_unfused = 0;
+    int32_t max_in = 0, max_out = 0;
+
+    for (int32_t s = 0; s < S; s++) {
+        const int64_t lo = first[s], hi = first[(size_t)s + 1];
+        // bandwidth constraint of section 3.3
+        std::fill(load.begin(), load.end(), 0);
+        for (int64_t q = lo; q < hi; q++) {
+            const sccl_send_t& t = sched->sends[order[(size_t)q]];
+            for (int32_t ci : covering[(size_t)t.src * P + t.dst]) load[(size_t)ci]++;
+        }
+        for (int32_t i = 0; i < topo->num_bw; i++)
+            if (load[(size_t)i] > (int64_t)topo->bw[i].chunks_per_round * sched->rounds[s]) return SCCL_ERR_BANDWIDTH;
+        // every value read must be present at the start of the step
+        for (int64_t q = lo; q < hi; q++) {
+            const sccl_send_t& t = sched->sends[order[(size_t)q]];
+            if (!held[(size_t)t.chunk * P + t.src]) return SCCL_ERR_SEND_NO_SOURCE;
+            if (t.op == SCCL_REDUCE_SUM && !held[(size_t)t.chunk * P + t.dst]) return SCCL_ERR_SEND_NO_SOURCE;
+        }
+        // hazards: with none, executing the ops one after the other equals "all reads see the start of the step"
+        for (int64_t q = lo; q < hi; q++) {
+            const sccl_send_t& t = sched->sends[order[(size_t)q]];
+            is_read[(size_t)t.chunk * P + t.src] = 1;
+        }
+        sccl_status_t hazard = SCCL_OK;
+        for (int64_t q = lo; q < hi && hazard == SCCL_OK; q++) {
+            const sccl_send_t& t = sched->sends[order[(size_t)q]];
+            const size_t d = (size_t)t.chunk * P + t.dst;
+            if (is_read[d]) hazard = SCCL_ERR_HAZARD;
+            else if (t.op == SCCL_COPY) {
+                if (is_written[d]) hazard = SCCL_ERR_HAZARD;
+                is_written[d] = 1;
+            } else {
+                if (is_written[d] == 1) hazard = SCCL_ERR_HAZARD;
+                is_written[d] = 2;
+            }
+        }
+        for (int64_t q = lo; q < hi; q++) {
+            const sccl_send_t& t = sched->sends[order[(size_t)q]];
+            is_read[(size_t)t.chunk * P + t.src] = 0;
+            is_written[(size_t)t.chunk * P + t.dst] = 0;
+        }
+        if (hazard != SCCL_OK) return hazard;
+
+        // apply the step to the contribution sets and form the groups
+        std::vector<std::pair<size_t, uint64_t>> updates;      // deferred: all reads see the start of the step
+        std::vector<size_t> consumed;
+        std::map<std::pair<int32_t, size_t>, size_t> index;    // (kind, c*P + anchor) -> position in `groups`
+        std::vector<Group> groups;
+        std::map<size_t, uint64_t> reduced;                    // running union per reduce destination
+        for (int64_t q = lo; q < hi; q++) {
+            const sccl_send_t& t = sched->sends[order[(size_t)q]];
+            const size_t src = (size_t)t.chunk * P + t.src, dst = (size_t)t.chunk * P + t.dst;
+            if (t.op == SCCL_COPY) {
+                updates.emplace_back(dst, held[src]);
+                auto key = std::make_pair((int32_t)0, src);
+                auto it = index.find(key);
+                if (it == index.end()) {
+                    index[key] = groups.size();
+                    groups.push_back(Group{0, t.chunk, t.src, {t.dst}});
+                } else {
+                    groups[it->second].others.push_back(t.dst);
+                }
+                chunks_unfused += 2;
+            } else {
+                auto r = reduced.find(dst);
+                uint64_t cur = (r == reduced.end()) ? held[dst] : r->second;
+                if (cur & held[src]) return SCCL_ERR_HAZARD;   // some rank would be counted twice
+                reduced[dst] = cur | held[src];
+                consumed.push_back(src);
+                auto key = std::make_pair((int32_t)1, dst);
+                auto it = index.find(key);
+                if (it == index.end()) {
+                    index[key] = groups.size();
+                    groups.push_back(Group{1, t.chunk, t.dst, {t.src}});
+                } else {
+                    groups[it->second].others.push_back(t.src);
+                }
+                chunks_unfused += 3;
+            }
+        }
+        for (auto& u : updates) held[u.first] = u.second;
+        for (auto& r : reduced) held[r.first] = r.second;
+        for (size_t c : consumed) held[c] = 0;
+        for (Group& g : groups) {
+            const int32_t k = (int32_t)g.others.size();
+            if (g.kind == 0) { n_copy_groups++; chunks_min += 1 + k; max_out = std::max(max_out, k); }
+            else             { n_reduce_groups++; chunks_min += k + 2; max_in = std::max(max_in, k); }
+            per_chunk[(size_t)g.chunk].push_back(std::move(g));
+        }
+    }
+    for (int32_t c = 0; c < G; c++)
+        for (int32_t n = 0; n < P; n++)
+            if (coll->post[(size_t)c * P + n] && held[(size_t)c * P + n] != everyone) return SCCL_ERR_POSTCONDITION;
+
+    // ---- emit the program, with streaming marks on accesses whose data is not reused
+    const bool hints = !(opts && opts->cache_hints == 1);
+    plan->prog.clear();
+    plan->chunk_off.assign((size_t)G + 1, 0);
+    struct Access { size_t word; bool reads; };
+    for (int32_t c = 0; c < G; c++) {
+        plan->chunk_off[(size_t)c] = (int32_t)plan->prog.size();
+        std::vector<std::vector<Access>> by_rank((size_t)P);     // this chunk's accesses per rank, in program order
+        for (const Group& g : per_chunk[(size_t)c]) {
+            const size_t base = plan->prog.size();
+            plan->prog.push_back(g.kind | ((int32_t)g.others.size() << 8));
+            plan->prog.push_back(g.anchor);
+            for (int32_t o : g.others) plan->prog.push_back(o);
+            // copy: the anchor (source) is read, the others are written
+            // reduce: the others (sources) are read; the anchor (destination) is read, then written
+            by_rank[(size_t)g.anchor].push_back({base + 1, true});
+            for (size_t j = 0; j < g.others.size(); j++)
+                by_rank[(size_t)g.others[j]].push_back({base + 2 + j, g.kind == OP_KIND_REDUCE});
+        }
+        if (!hints) continue;
+        // An access is marked streaming when the NEXT access of this program to the same (c, n)
+        // does not read it (it is overwritten, or never touched again): nothing gains from
+        // keeping that data in the caches.
+        for (int32_t n = 0; n < P; n++) {
+            const std::vector<Access>& acc = by_rank[(size_t)n];
+            for (size_t i = 0; i < acc.size(); i++)
+                if (i + 1 == acc.size() || !acc[i + 1].reads) plan->prog[acc[i].word] |= OPERAND_STREAM;
+        }
+    }
+    plan->chunk_off[(size_t)G] = (int32_t)plan->prog.size();
+
+    // ---- record the problem and the statistics
+    plan->P = P; plan->G = G; plan->S = S;
+    plan->dtype = coll->dtype;
+    plan->combining = coll->combining;
+    plan->elems_per_chunk = coll->elems_per_chunk;
+    plan->rounds.assign(sched->rounds, sched->rounds + S);
+    if (opts) plan->opts = *opts;
+    const int64_t chunk_bytes = coll->elems_per_chunk * elem_bytes(coll->dtype);
+    sccl_stats_t& st = plan->stats;
+    st.num_nodes = P; st.num_global_chunks = G;
+    st.num_steps = S; st.num_rounds = (int32_t)R; st.k = (int32_t)(R - S);
+    st.num_sends = N;
+    st.num_copy_groups = n_copy_groups; st.num_reduce_groups = n_reduce_groups;
+    st.max_fan_in = max_in; st.max_fan_out = max_out;
+    st.chunk_bytes = chunk_bytes;
+    st.bytes_per_rank = chunk_bytes * G;
+    st.bytes_min = chunks_min * chunk_bytes;
+    st.bytes_unfused = chunks_unfused * chunk_bytes;
+
+    // ---- launch shape: how the element range of a chunk is cut into tiles (work distribution per chunk size)
+    int32_t W = 16;
+    while (W > elem_bytes(coll->dtype) && chunk_bytes % W != 0) W >>= 1;
+    plan->vector_bytes = W;
+    plan->vecs_per_chunk = chunk_bytes / W;
+    int32_t bt = (opts && opts->block_threads) ? opts->block_threads : 256;
+    int32_t vt = (opts && opts->vectors_per_thread) ? opts->vectors_per_thread : 2;
+    auto items_for = [&](int32_t b, int32_t v) {
+        const int64_t tile = (int64_t)b * v;
+        return (int64_t)G * ((plan->vecs_per_chunk + tile - 1) / tile);
+    };
+    // small chunks: shrink the tile until there are enough work items to occupy the CUs
+    const int64_t want = (int64_t)8 * (num_cus > 0 ? num_cus : 256);
+    if (!(opts && opts->vectors_per_thread))
+        while (vt > 1 && items_for(bt, vt) < want) vt >>= 1;
+    if (!(opts && opts->block_threads))
+        while (bt > 64 && items_for(bt, vt) < want) bt >>= 1;
+    plan->block_threads = bt;
+    plan->vectors_per_thread = vt;
+    const int64_t tile = (int64_t)bt * vt;
+    const int64_t tiles = (plan->vecs_per_chunk + tile - 1) / tile;
+    if (tiles > 0x7fffffff) return SCCL_ERR_INVALID_ARG;
+    plan->tiles_per_chunk = (int32_t)tiles;
+    plan->num_items = (int64_t)G * tiles;
+    st.vector_bytes = W;
+    st.block_threads = bt;
+    st.vectors_per_thread = vt;
+    st.num_work_items = plan->num_items;
+    st.grid_workgroups = 0;
+    return SCCL_OK;
+}

@@ -1,0 +1,53 @@
+// Internal: the compiled plan shared by the host compiler (plan.cpp) and the device side (exec.hip).
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "sccl.h"
+
+// Device step table ("program"): one op list per chunk, ops in step order.
+// Ops of different chunks never touch the same memory (chunk c lives at the
+// same offset in every rank buffer), so the only ordering the schedule imposes
+// is between the ops of ONE chunk.  An op is
+//   word 0      : kind (bit 0: 0 copy group, 1 reduce group) | count << 8
+//   word 1      : copy: the source rank          reduce: the destination rank
+//   word 2..    : copy: `count` destination ranks reduce: `count` source ranks, in schedule order
+// Each operand word is  rank | flags << 16 ; flag bit 0 (OPERAND_STREAM) marks
+// an access whose data is not touched again by this chunk's program before it
+// is overwritten (or ever): it may bypass the caches' reuse policy.
+constexpr int32_t OP_KIND_REDUCE = 1;
+constexpr int32_t OPERAND_RANK_MASK = 0xffff;
+constexpr int32_t OPERAND_STREAM = 1 << 16;
+
+struct sccl_plan {
+    // problem
+    int32_t P = 0, G = 0, S = 0;
+    sccl_dtype_t dtype = SCCL_F32;
+    int32_t combining = 0;
+    int64_t elems_per_chunk = 0;
+    std::vector<int32_t> rounds;
+    // compiled program (host copy)
+    std::vector<int32_t> prog;
+    std::vector<int32_t> chunk_off;     // G + 1 offsets into prog
+    sccl_stats_t stats{};
+    sccl_options_t opts{};
+    // launch shape
+    int32_t vector_bytes = 16;
+    int32_t block_threads = 256;
+    int32_t vectors_per_thread = 2;
+    int64_t vecs_per_chunk = 0;
+    int32_t tiles_per_chunk = 0;
+    int64_t num_items = 0;
+    int32_t grid = 0;
+    // device side (owned)
+    int device = -1;
+    int32_t* d_prog = nullptr;
+    int32_t* d_chunk_off = nullptr;
+};
+
+// Validates the schedule and fills everything except the device fields and `grid`.
+// num_cus is the CU count the launch shape is sized for.
+sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collective_t* coll,
+                                const sccl_schedule_t* sched, const sccl_options_t* opts, int num_cus,
+                                sccl_plan* plan);

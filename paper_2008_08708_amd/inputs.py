@@ -138,4 +138,25 @@ def torch_generate(dist: str, dtype: str, seed: int, rank: int, start: int, coun
         return (u24 * (2.0 ** -23) - 1.0).to(tdt)
     if dist == "smallint":
         return (lsr(r, 40) % 17 - 8).to(tdt)
+    if dist == "normal":
+        # same recipe as generate(); log/cos come from the device's libm, so the last bit of the
+        # double may differ from numpy's: a caller that compares against host code reads these back
+        key2 = int(_mix(np.array([(seed * 0x1000003 + rank * 0x10001 + 0x101 + 1) & 0xFFFFFFFFFFFFFFFF],
+                                 dtype=np.uint64))[0])
+        r2 = mix(idx * s64(int(_GOLD)) + s64(key2))
+        u1 = (lsr(r, 11).to(torch.float64) + 1.0) * (2.0 ** -53)
+        u2 = lsr(r2, 11).to(torch.float64) * (2.0 ** -53)
+        z = torch.sqrt(-2.0 * torch.log(u1)) * torch.cos(2.0 * np.pi * u2)
+        return z.to(tdt)
     raise ValueError(f"{dist} has no device generator")
+
+
+def torch_rank_buffer(dist: str, dtype: str, seed: int, rank: int, num_elems: int, device, slab: int = 1 << 25):
+    """A whole rank buffer on `device`, generated slab by slab to bound the temporaries."""
+    import torch
+    tdt = {"i32": torch.int32, "f32": torch.float32, "f16": torch.float16}[dtype]
+    out = torch.empty(num_elems, dtype=tdt, device=device)
+    for s in range(0, num_elems, slab):
+        n = min(slab, num_elems - s)
+        out[s:s + n] = torch_generate(dist, dtype, seed, rank, s, n, device)
+    return out

@@ -1,0 +1,249 @@
+"""ctypes binding of libsccl.so: the same names as include/sccl.h, argument marshalling only.
+
+Every step of the hot path runs in the library's kernels; nothing here computes.
+There is no CPU fallback: if the library is missing the import of a function fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsccl.so")
+
+SCCL_MAX_RANKS = 64
+SCCL_OK = 0
+STATUS_NAMES = ["SCCL_OK", "SCCL_ERR_INVALID_ARG", "SCCL_ERR_TOPOLOGY", "SCCL_ERR_SEND_NO_SOURCE",
+                "SCCL_ERR_SEND_NO_LINK", "SCCL_ERR_BANDWIDTH", "SCCL_ERR_POSTCONDITION", "SCCL_ERR_HAZARD",
+                "SCCL_ERR_ALIGNMENT", "SCCL_ERR_OVERLAP", "SCCL_ERR_NOMEM", "SCCL_ERR_DEVICE"]
+SCCL_I32, SCCL_F32, SCCL_F16 = 0, 1, 2
+DTYPE_CODES = {"i32": SCCL_I32, "f32": SCCL_F32, "f16": SCCL_F16}
+SCCL_COPY, SCCL_REDUCE_SUM = 0, 1
+SCCL_PLAN_HOST_ONLY = 1
+
+
+class sccl_edge_t(ctypes.Structure):
+    _fields_ = [("src", ctypes.c_int32), ("dst", ctypes.c_int32)]
+
+
+class sccl_bw_t(ctypes.Structure):
+    _fields_ = [("edges", ctypes.POINTER(sccl_edge_t)), ("num_edges", ctypes.c_int32),
+                ("chunks_per_round", ctypes.c_int32)]
+
+
+class sccl_topology_t(ctypes.Structure):
+    _fields_ = [("num_nodes", ctypes.c_int32), ("bw", ctypes.POINTER(sccl_bw_t)), ("num_bw", ctypes.c_int32)]
+
+
+class sccl_collective_t(ctypes.Structure):
+    _fields_ = [("num_global_chunks", ctypes.c_int32), ("pre", ctypes.c_void_p), ("post", ctypes.c_void_p),
+                ("combining", ctypes.c_int32), ("dtype", ctypes.c_int32), ("elems_per_chunk", ctypes.c_int64)]
+
+
+class sccl_send_t(ctypes.Structure):
+    _fields_ = [("chunk", ctypes.c_int32), ("src", ctypes.c_int32), ("dst", ctypes.c_int32),
+                ("step", ctypes.c_int32), ("op", ctypes.c_int32)]
+
+
+class sccl_schedule_t(ctypes.Structure):
+    _fields_ = [("num_steps", ctypes.c_int32), ("rounds", ctypes.c_void_p), ("sends", ctypes.c_void_p),
+                ("num_sends", ctypes.c_int64)]
+
+
+class sccl_options_t(ctypes.Structure):
+    _fields_ = [("flags", ctypes.c_uint32), ("block_threads", ctypes.c_int32),
+                ("vectors_per_thread", ctypes.c_int32), ("max_workgroups", ctypes.c_int32),
+                ("cache_hints", ctypes.c_int32)]
+
+
+class sccl_stats_t(ctypes.Structure):
+    _fields_ = [("num_nodes", ctypes.c_int32), ("num_global_chunks", ctypes.c_int32),
+                ("num_steps", ctypes.c_int32), ("num_rounds", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("num_sends", ctypes.c_int64), ("num_copy_groups", ctypes.c_int64),
+                ("num_reduce_groups", ctypes.c_int64), ("max_fan_in", ctypes.c_int32),
+                ("max_fan_out", ctypes.c_int32), ("chunk_bytes", ctypes.c_int64),
+                ("bytes_per_rank", ctypes.c_int64), ("bytes_min", ctypes.c_int64),
+                ("bytes_unfused", ctypes.c_int64), ("vector_bytes", ctypes.c_int32),
+                ("block_threads", ctypes.c_int32), ("vectors_per_thread", ctypes.c_int32),
+                ("num_work_items", ctypes.c_int64), ("grid_workgroups", ctypes.c_int32)]
+
+    def as_dict(self):
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
+EXPORTS = ["sccl_plan_create", "sccl_plan_create_ex", "sccl_execute", "sccl_plan_stats", "sccl_plan_destroy",
+           "sccl_status_string", "sccl_copy_kernel"]
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2008_08708_amd.build` "
+                               "(or __graft_entry__.build()); this package has no CPU fallback")
+        # torch first: it brings its own copy of the HIP runtime (same soname as the system's), and the
+        # process must hold exactly one -- the one torch allocates device memory and streams with.
+        # Loaded after torch, this library's dependency resolves to that already-loaded runtime.
+        import torch  # noqa: F401
+        L = ctypes.CDLL(LIB_PATH)
+        L.sccl_plan_create.restype = ctypes.c_int
+        L.sccl_plan_create.argtypes = [ctypes.POINTER(sccl_topology_t), ctypes.POINTER(sccl_collective_t),
+                                       ctypes.POINTER(sccl_schedule_t), ctypes.POINTER(ctypes.c_void_p)]
+        L.sccl_plan_create_ex.restype = ctypes.c_int
+        L.sccl_plan_create_ex.argtypes = [ctypes.POINTER(sccl_topology_t), ctypes.POINTER(sccl_collective_t),
+                                          ctypes.POINTER(sccl_schedule_t), ctypes.POINTER(sccl_options_t),
+                                          ctypes.POINTER(ctypes.c_void_p)]
+        L.sccl_execute.restype = ctypes.c_int
+        L.sccl_execute.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p]
+        L.sccl_plan_stats.restype = ctypes.c_int
+        L.sccl_plan_stats.argtypes = [ctypes.c_void_p, ctypes.POINTER(sccl_stats_t)]
+        L.sccl_plan_destroy.restype = None
+        L.sccl_plan_destroy.argtypes = [ctypes.c_void_p]
+        L.sccl_status_string.restype = ctypes.c_char_p
+        L.sccl_status_string.argtypes = [ctypes.c_int]
+        L.sccl_copy_kernel.restype = ctypes.c_int
+        L.sccl_copy_kernel.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        _lib = L
+    return _lib
+
+
+class ScclError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        self.name = sccl_status_string(status)
+        super().__init__(f"{where}: {self.name}")
+
+
+# ---- plain descriptions of the three inputs (host data only; what sccl_plan_create marshals)
+
+@dataclass
+class Topology:
+    num_nodes: int
+    bw: List[Tuple[List[Tuple[int, int]], int]]          # [(edges, chunks_per_round)]
+
+
+@dataclass
+class Collective:
+    num_global_chunks: int
+    pre: np.ndarray                                       # G x P of 0/1
+    post: np.ndarray
+    combining: bool
+    dtype: str                                            # "i32" | "f32" | "f16"
+    elems_per_chunk: int
+
+
+@dataclass
+class Schedule:
+    rounds: List[int]
+    sends: np.ndarray                                     # (n, 5) int32: chunk, src, dst, step, op
+
+
+class Plan:
+    """Owns an sccl_plan_t*; freed by sccl_plan_destroy or when collected."""
+
+    def __init__(self, handle: int):
+        self.handle = ctypes.c_void_p(handle)
+
+    def __del__(self):
+        try:
+            sccl_plan_destroy(self)
+        except Exception:
+            pass
+
+
+def sccl_status_string(status: int) -> str:
+    return lib().sccl_status_string(int(status)).decode()
+
+
+def sccl_plan_create(topology: Topology, collective: Collective, schedule: Schedule,
+                     options: Optional[dict] = None) -> Plan:
+    """sccl_plan_create / sccl_plan_create_ex: marshal the three descriptions and return the plan.
+
+    options: dict with any of flags, block_threads, vectors_per_thread, max_workgroups, cache_hints.
+    Raises ScclError carrying the library's status on failure.
+    """
+    L = lib()
+    keep = []                                              # keeps the ctypes arrays alive during the call
+    bws = (sccl_bw_t * max(1, len(topology.bw)))()
+    for i, (edges, b) in enumerate(topology.bw):
+        arr = (sccl_edge_t * max(1, len(edges)))()
+        for j, (s, d) in enumerate(edges):
+            arr[j].src, arr[j].dst = int(s), int(d)
+        keep.append(arr)
+        bws[i].edges = ctypes.cast(arr, ctypes.POINTER(sccl_edge_t))
+        bws[i].num_edges = len(edges)
+        bws[i].chunks_per_round = int(b)
+    topo = sccl_topology_t(int(topology.num_nodes), ctypes.cast(bws, ctypes.POINTER(sccl_bw_t)), len(topology.bw))
+    pre = np.ascontiguousarray(collective.pre, dtype=np.uint8)
+    post = np.ascontiguousarray(collective.post, dtype=np.uint8)
+    coll = sccl_collective_t(int(collective.num_global_chunks), pre.ctypes.data, post.ctypes.data,
+                             int(bool(collective.combining)), DTYPE_CODES[collective.dtype],
+                             int(collective.elems_per_chunk))
+    rounds = np.ascontiguousarray(schedule.rounds, dtype=np.int32)
+    sends = np.ascontiguousarray(schedule.sends, dtype=np.int32).reshape(-1, 5)
+    sched = sccl_schedule_t(len(rounds), rounds.ctypes.data, sends.ctypes.data, sends.shape[0])
+    out = ctypes.c_void_p()
+    if options:
+        o = sccl_options_t(**{k: int(v) for k, v in options.items()})
+        st = L.sccl_plan_create_ex(ctypes.byref(topo), ctypes.byref(coll), ctypes.byref(sched), ctypes.byref(o),
+                                   ctypes.byref(out))
+    else:
+        st = L.sccl_plan_create(ctypes.byref(topo), ctypes.byref(coll), ctypes.byref(sched), ctypes.byref(out))
+    if st != SCCL_OK:
+        raise ScclError(st, "sccl_plan_create")
+    return Plan(out.value)
+
+
+def _device_ptr(b) -> int:
+    if hasattr(b, "data_ptr"):
+        return int(b.data_ptr())
+    return int(b)
+
+
+def sccl_execute(plan: Plan, rank_buffers: Sequence, stream=None) -> None:
+    """Enqueue the plan on `stream` (a torch stream, a raw hipStream_t value, or None for torch's current stream).
+
+    rank_buffers: P device tensors (or raw device addresses).
+    """
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    ptrs = (ctypes.c_void_p * len(rank_buffers))(*[_device_ptr(b) for b in rank_buffers])
+    st = lib().sccl_execute(plan.handle, ptrs, ctypes.c_void_p(int(stream)))
+    if st != SCCL_OK:
+        raise ScclError(st, "sccl_execute")
+
+
+def sccl_plan_stats(plan: Plan) -> dict:
+    s = sccl_stats_t()
+    st = lib().sccl_plan_stats(plan.handle, ctypes.byref(s))
+    if st != SCCL_OK:
+        raise ScclError(st, "sccl_plan_stats")
+    return s.as_dict()
+
+
+def sccl_plan_destroy(plan: Plan) -> None:
+    if plan.handle:
+        lib().sccl_plan_destroy(plan.handle)
+        plan.handle = ctypes.c_void_p()
+
+
+def sccl_copy_kernel(dst, src, nbytes: int, stream=None) -> None:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    st = lib().sccl_copy_kernel(ctypes.c_void_p(_device_ptr(dst)), ctypes.c_void_p(_device_ptr(src)),
+                                ctypes.c_size_t(int(nbytes)), ctypes.c_void_p(int(stream)))
+    if st != SCCL_OK:
+        raise ScclError(st, "sccl_copy_kernel")

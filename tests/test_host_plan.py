@@ -1,0 +1,191 @@
+"""CPU tests of the library's host side: it loads, exports what include/sccl.h declares, and its
+validation agrees with the oracle's verdict on good and bad plans (no kernel is launched here)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from helpers import VERDICT_TO_STATUS, plan_status
+from oracle import collective as col
+from oracle import executor as ex
+from oracle import generate as gen
+from oracle import topology as tp
+from oracle.schedule import COPY, REDUCE, Schedule, make_schedule
+from oracle.validate import validate
+from paper_2008_08708_amd import sccl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "sccl.h")).read()
+    declared = set(re.findall(r"\b(sccl_[a-z_]+)\s*\(", header))
+    assert declared == set(sccl.EXPORTS)
+    L = sccl.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert sccl.sccl_status_string(0) == "SCCL_OK"
+    for i, name in enumerate(sccl.STATUS_NAMES):
+        assert sccl.sccl_status_string(i) == name
+        assert re.search(r"\b%s = %d\b" % (name, i), header)
+
+
+def test_struct_layouts_match_the_header():
+    # sizes a C compiler gives the structs of include/sccl.h on this ABI
+    assert ctypes.sizeof(sccl.sccl_edge_t) == 8
+    assert ctypes.sizeof(sccl.sccl_bw_t) == 16
+    assert ctypes.sizeof(sccl.sccl_topology_t) == 24
+    assert ctypes.sizeof(sccl.sccl_collective_t) == 40
+    assert ctypes.sizeof(sccl.sccl_send_t) == 20
+    assert ctypes.sizeof(sccl.sccl_schedule_t) == 32
+    assert ctypes.sizeof(sccl.sccl_options_t) == 20
+
+
+GOOD = [
+    (tp.ring(4), 1, "greedy"), (tp.hcm8(), 1, "greedy"), (tp.hcm8(), 2, "greedy"), (tp.dgx1(), 2, "greedy"),
+    (tp.torus2d(4, 4), 4, "greedy"), (tp.ring(8), 2, "ring"), (tp.ring(8), 4, "ring"), (tp.complete(5), 2, "greedy"),
+]
+
+
+@pytest.mark.parametrize("topo,C,kind", GOOD)
+def test_valid_plans_are_accepted_and_counted_like_the_oracle(topo, C, kind):
+    P = topo.num_nodes
+    ag = col.allgather(P, C)
+    s = gen.ring_allgather(P, C) if kind == "ring" else gen.greedy_bfs(topo, ag)
+    ar, arc = gen.compose_allreduce(s, ag)
+    rs, rsc = gen.reducescatter_from(s, ag)
+    for (coll, sched, dtype, epc) in ((ag, s, "i32", 1000), (arc, ar, "f32", 1000), (rsc, rs, "f16", 1000)):
+        assert validate(topo, coll, sched).ok
+        name, st = plan_status(topo, coll, sched, dtype, epc)
+        assert name == "SCCL_OK"
+        cs = epc * (2 if dtype == "f16" else 4)
+        fused, unfused = ex.algorithmic_bytes(sched, cs)
+        assert (st["bytes_min"], st["bytes_unfused"]) == (fused, unfused)
+        assert (st["num_steps"], st["num_rounds"], st["k"]) == (sched.num_steps, sched.num_rounds, sched.k)
+        assert st["num_sends"] == sched.sends.shape[0]
+        assert st["chunk_bytes"] == cs and st["bytes_per_rank"] == cs * coll.num_chunks
+
+
+def test_headline_plan_statistics():
+    ag = col.allgather(8, 1)
+    ar, arc = gen.compose_allreduce(gen.greedy_bfs(tp.hcm8(), ag), ag)
+    name, st = plan_status(tp.hcm8(), arc, ar, "f32", (32 << 20) // 4)
+    assert name == "SCCL_OK"
+    assert st["num_sends"] == 112 and st["num_steps"] == 4 and st["bytes_unfused"] == int(8.75 * 2 ** 30)
+    assert st["bytes_per_rank"] == 256 << 20
+    assert st["vector_bytes"] == 16 and st["num_work_items"] * st["block_threads"] * st["vectors_per_thread"] * 16 == 8 * (32 << 20)
+
+
+def bad_plans():
+    t3, ag3 = tp.ring(3), col.allgather(3, 1)
+    good = [(n, n, (n + 1) % 3, 0) for n in range(3)] + [(n, n, (n - 1) % 3, 0) for n in range(3)]
+    R, C = REDUCE, COPY
+    ar3 = col.allreduce(3, 1)
+    k4, bc4 = tp.complete(4), col.broadcast(4, 1, 0)
+    yield t3, ag3, make_schedule([1], good)
+    yield t3, ag3, make_schedule([1], [(3, 0, 1, 0)])
+    yield t3, ag3, make_schedule([1], [(0, 0, 3, 0)])
+    yield t3, ag3, make_schedule([1], [(0, 0, 1, 1)])
+    yield t3, ag3, make_schedule([0], good)
+    yield t3, ag3, make_schedule([1], [(0, 0, 0, 0)])
+    yield t3, ag3, make_schedule([1], [(0, 0, 1, 0, 7)])
+    yield t3, ag3, make_schedule([1], [(0, 0, 1, 0, R)])
+    yield tp.ring(4), col.allgather(4, 1), make_schedule([1], [(0, 0, 2, 0)])
+    yield t3, ag3, make_schedule([1], [(0, 1, 2, 0)])
+    yield tp.ring(4), col.allgather(4, 1), make_schedule([1], [(0, 0, 1, 0), (0, 1, 2, 0)])
+    yield t3, col.allgather(3, 2), make_schedule([1], [(0, 0, 1, 0), (3, 0, 1, 0)])
+    yield t3, col.allgather(3, 2), make_schedule([2], [(0, 0, 1, 0), (3, 0, 1, 0)])
+    yield t3, ag3, make_schedule([1], good[:-1])
+    yield k4, bc4, make_schedule([1, 1], [(0, 0, 1, 0), (0, 0, 2, 0), (0, 1, 3, 1), (0, 2, 3, 1)])
+    yield tp.shared_bus(3), ag3, make_schedule([1], good)
+    yield tp.shared_bus(3), ag3, make_schedule([6], good)
+    yield t3, ar3, make_schedule([1, 1, 1], [(0, 2, 1, 0, R), (0, 1, 0, 1, R), (0, 0, 1, 2, C), (0, 0, 2, 2, C)])
+    yield t3, ar3, make_schedule([1, 1], [(0, 2, 1, 0, R), (0, 1, 0, 0, R), (0, 0, 1, 1, C), (0, 0, 2, 1, C)])
+    yield t3, ar3, make_schedule([1, 1, 1], [(0, 2, 1, 0, R), (0, 2, 0, 0, R), (0, 1, 0, 1, R), (0, 0, 1, 2, C), (0, 0, 2, 2, C)])
+    yield t3, ar3, make_schedule([1, 1, 1], [(0, 2, 1, 0, R), (0, 2, 0, 1, R), (0, 1, 0, 2, R)])
+    yield t3, ar3, make_schedule([1, 1], [(0, 1, 0, 0, R), (0, 0, 1, 1, C), (0, 0, 2, 1, C)])
+    yield t3, ar3, make_schedule([1], [(0, 1, 0, 0, C), (0, 2, 0, 0, R)])
+    yield tp.ring(4), col.allgather(4, 1), gen.recursive_doubling_ring4()
+    yield tp.ring(4), col.allgather(4, 1), Schedule([1, 1], gen.recursive_doubling_ring4().sends)
+    # zero-bandwidth constraint blocks a link
+    tz = tp.Topology(3, tuple(tp.ring(3).bw) + ((frozenset([(0, 1)]), 0),))
+    yield tz, ag3, make_schedule([1], good)
+
+
+@pytest.mark.parametrize("i,case", list(enumerate(bad_plans())))
+def test_verdict_agrees_with_the_oracle(i, case):
+    topo, coll, sched = case
+    want = VERDICT_TO_STATUS[validate(topo, coll, sched).verdict.value]
+    got, _ = plan_status(topo, coll, sched)
+    assert got == want
+
+
+def test_mutated_valid_schedules_get_the_same_verdict():
+    # random single-field mutations of a valid Allreduce: the library and the oracle must agree on every one
+    rng = np.random.default_rng(7)
+    topo = tp.hcm8()
+    ag = col.allgather(8, 1)
+    ar, arc = gen.compose_allreduce(gen.greedy_bfs(topo, ag), ag)
+    seen = set()
+    for trial in range(300):
+        sends = ar.sends.copy()
+        i = rng.integers(0, sends.shape[0])
+        f = rng.integers(0, 5)
+        sends[i, f] = rng.integers(-1, 9) if f < 3 else (rng.integers(-1, 5) if f == 3 else rng.integers(0, 3))
+        m = Schedule(list(ar.rounds), sends)
+        want = VERDICT_TO_STATUS[validate(topo, arc, m).verdict.value]
+        got, _ = plan_status(topo, arc, m)
+        assert got == want, (i, f, sends[i])
+        seen.add(got)
+    assert len(seen) >= 5          # the mutations really exercise several error paths
+
+
+def test_malformed_topology_and_arguments():
+    t3, ag3 = tp.ring(3), col.allgather(3, 1)
+    good = make_schedule([1], [(n, n, (n + 1) % 3, 0) for n in range(3)] + [(n, n, (n - 1) % 3, 0) for n in range(3)])
+    bad_t = tp.Topology(3, ((frozenset([(0, 5)]), 1),))
+    assert plan_status(bad_t, ag3, good)[0] == "SCCL_ERR_TOPOLOGY"
+    bad_t = tp.Topology(3, ((frozenset([(1, 1)]), 1),))
+    assert plan_status(bad_t, ag3, good)[0] == "SCCL_ERR_TOPOLOGY"
+    bad_t = tp.Topology(3, ((frozenset([(0, 1)]), -1),))
+    assert plan_status(bad_t, ag3, good)[0] == "SCCL_ERR_TOPOLOGY"
+    assert plan_status(t3, ag3, good, options={"block_threads": 100})[0] == "SCCL_ERR_INVALID_ARG"
+    assert plan_status(t3, ag3, good, options={"vectors_per_thread": 3})[0] == "SCCL_ERR_INVALID_ARG"
+    assert plan_status(t3, ag3, good, elems_per_chunk=-1)[0] == "SCCL_ERR_INVALID_ARG"
+    big = tp.ring(65)
+    assert plan_status(big, col.allgather(65, 1), gen.greedy_bfs(big, col.allgather(65, 1)))[0] == "SCCL_ERR_INVALID_ARG"
+    ok64 = tp.ring(64)
+    assert plan_status(ok64, col.allgather(64, 1), gen.greedy_bfs(ok64, col.allgather(64, 1)))[0] == "SCCL_OK"
+
+
+def test_execute_on_host_only_plan_is_refused():
+    t3, ag3 = tp.ring(3), col.allgather(3, 1)
+    good = make_schedule([1], [(n, n, (n + 1) % 3, 0) for n in range(3)] + [(n, n, (n - 1) % 3, 0) for n in range(3)])
+    from helpers import to_binding
+    p = sccl.sccl_plan_create(*to_binding(t3, ag3, good, "f32", 4), options={"flags": sccl.SCCL_PLAN_HOST_ONLY})
+    with pytest.raises(sccl.ScclError) as e:
+        sccl.sccl_execute(p, [16, 32, 48], stream=0)
+    assert e.value.name == "SCCL_ERR_DEVICE"
+    sccl.sccl_plan_destroy(p)
+
+
+@pytest.mark.parametrize("dtype,epc,want_w", [("f32", 4, 16), ("f32", 6, 8), ("f32", 5, 4), ("f16", 8, 16), ("f16", 4, 8),
+                                               ("f16", 2, 4), ("f16", 3, 2), ("i32", 1, 4), ("f32", 0, 16)])
+def test_vector_width_follows_the_chunk_size(dtype, epc, want_w):
+    t3, ag3 = tp.ring(3), col.allgather(3, 1)
+    good = make_schedule([1], [(n, n, (n + 1) % 3, 0) for n in range(3)] + [(n, n, (n - 1) % 3, 0) for n in range(3)])
+    name, st = plan_status(t3, ag3, good, dtype, epc)
+    assert name == "SCCL_OK" and st["vector_bytes"] == want_w
+
+
+def test_work_distribution_shrinks_tiles_for_small_chunks():
+    topo = tp.torus2d(4, 4)
+    ag = col.allgather(16, 4)
+    s = gen.greedy_bfs(topo, ag)
+    _, tiny = plan_status(topo, ag, s, "f32", 4)                 # 16-byte chunks: one vector each
+    assert (tiny["block_threads"], tiny["vectors_per_thread"], tiny["num_work_items"]) == (64, 1, 64)
+    _, big = plan_status(topo, ag, s, "f32", (16 << 20) // 4)
+    assert (big["block_threads"], big["vectors_per_thread"]) == (256, 2)
+    assert big["num_work_items"] == 64 * ((16 << 20) // (256 * 2 * 16))
