@@ -22,6 +22,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
+# Bytes that left the L2 per launch, from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each scaled by
+# what the same counter reads for the 1 GiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  Keyed by
+# (workload, grid, block_threads, vectors_per_thread); the figures and commands are in profiles/.
+MEASURED_TRAFFIC = {
+    ("cfg3", 256, 256, 4): (2 * 1095450.0 + 2664775.8) * 1024,
+}
+
 
 def make_inputs(wl, sf, device):
     """Pristine device buffers for a workload (seeded, generated on the device; bit-identical to the host recipe
@@ -186,7 +193,9 @@ def main():
         "ms_min": round(min(ms), 4), "ms_median": round(sorted(ms)[len(ms) // 2], 4),
         "wall_ms_per_step_incl_restore": round(run["wall_s"] * 1e3 / args.steps, 4),
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(gbs / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC.get((args.workload, st["grid_workgroups"], st["block_threads"],
+                                                      st["vectors_per_thread"])),
                      "kernel": "sccl_exec_kernel (one launch = the whole schedule)",
                      "algorithmic_bytes_per_launch": st["bytes_min"]},
     }

@@ -118,9 +118,10 @@ typedef struct {
 typedef struct {
     uint32_t flags;
     int32_t block_threads;         /* 0 = choose from the chunk size; else 64, 128 or 256 */
-    int32_t vectors_per_thread;    /* 0 = choose; else 1, 2 or 4: vectors each lane moves per operand */
-    int32_t max_workgroups;        /* 0 = choose from the device's CU count; else an upper bound on the grid */
-    int32_t cache_hints;           /* 0 = default (on); 1 = off; 2 = on: streaming loads/stores for data touched once */
+    int32_t vectors_per_thread;    /* 0 = choose; else 1, 2, 4 or 8: vectors each lane moves per operand */
+    int32_t max_workgroups;        /* 0 = one workgroup per compute unit; else the grid size;
+                                      either way capped by the number of work items */
+    int32_t reserved;              /* must be 0 */
 } sccl_options_t;
 
 typedef struct {

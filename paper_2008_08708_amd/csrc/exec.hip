@@ -35,7 +35,6 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 template <int W> struct VecOf;
 template <> struct VecOf<16> { typedef u32x4 type; };
@@ -51,23 +50,66 @@ typedef const int32_t __attribute__((address_space(4)))* table_ptr;
 struct ExecArgs {
     const int32_t* prog;
     const int32_t* chunk_off;
-    int64_t vecs_per_chunk;
+    int64_t chunk_bytes;
     int64_t num_items;
     int32_t tiles_per_chunk;
     int32_t pad;
     char* bufs[SCCL_MAX_RANKS];
 };
 
-// ---- memory access.  The plan marks operands whose data is not reused (OPERAND_STREAM); the
-// kernel does not act on the mark yet: a run-time choice between a plain and a non-temporal
-// access of the same address is folded into one plain access by the compiler.
-template <typename V>
-__device__ __forceinline__ V load_vec(const char* p) {
-    return *reinterpret_cast<const V*>(p);
+// ---- memory access through buffer descriptors.
+// A descriptor covers exactly one tile of one rank's chunk (base = start of the tile, size = the
+// bytes of the tile that exist), so (1) the hardware's range check drops the lanes beyond a ragged
+// chunk end -- loads return 0, stores are discarded -- and no lane predicate is needed, (2) lane
+// offsets are small 32-bit numbers however large the buffers are, and addresses live in scalar
+// registers, which keeps the vector register count low.  All accesses use the default cache
+// policy: non-temporal loads and stores for data that is touched once were measured and lose
+// (they also evict what the next step re-reads).
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(char* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
 }
-template <typename V>
-__device__ __forceinline__ void store_vec(char* p, V v) {
-    *reinterpret_cast<V*>(p) = v;
+
+template <int W> struct BufIO;
+template <> struct BufIO<16> {
+    static __device__ __forceinline__ u32x4 ld(__amdgpu_buffer_rsrc_t r, uint32_t v, uint32_t s) {
+        auto x = __builtin_amdgcn_raw_buffer_load_b128(r, (int)v, (int)s, 0); u32x4 o; __builtin_memcpy(&o, &x, 16); return o; }
+    static __device__ __forceinline__ void st(u32x4 d, __amdgpu_buffer_rsrc_t r, uint32_t v, uint32_t s) {
+        decltype(__builtin_amdgcn_raw_buffer_load_b128(r, 0, 0, 0)) x; __builtin_memcpy(&x, &d, 16);
+        __builtin_amdgcn_raw_buffer_store_b128(x, r, (int)v, (int)s, 0); }
+};
+template <> struct BufIO<8> {
+    static __device__ __forceinline__ u32x2 ld(__amdgpu_buffer_rsrc_t r, uint32_t v, uint32_t s) {
+        auto x = __builtin_amdgcn_raw_buffer_load_b64(r, (int)v, (int)s, 0); u32x2 o; __builtin_memcpy(&o, &x, 8); return o; }
+    static __device__ __forceinline__ void st(u32x2 d, __amdgpu_buffer_rsrc_t r, uint32_t v, uint32_t s) {
+        decltype(__builtin_amdgcn_raw_buffer_load_b64(r, 0, 0, 0)) x; __builtin_memcpy(&x, &d, 8);
+        __builtin_amdgcn_raw_buffer_store_b64(x, r, (int)v, (int)s, 0); }
+};
+template <> struct BufIO<4> {
+    static __device__ __forceinline__ uint32_t ld(__amdgpu_buffer_rsrc_t r, uint32_t v, uint32_t s) {
+        return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, (int)v, (int)s, 0); }
+    static __device__ __forceinline__ void st(uint32_t d, __amdgpu_buffer_rsrc_t r, uint32_t v, uint32_t s) {
+        __builtin_amdgcn_raw_buffer_store_b32(d, r, (int)v, (int)s, 0); }
+};
+template <> struct BufIO<2> {
+    static __device__ __forceinline__ uint16_t ld(__amdgpu_buffer_rsrc_t r, uint32_t v, uint32_t s) {
+        return (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)v, (int)s, 0); }
+    static __device__ __forceinline__ void st(uint16_t d, __amdgpu_buffer_rsrc_t r, uint32_t v, uint32_t s) {
+        __builtin_amdgcn_raw_buffer_store_b16(d, r, (int)v, (int)s, 0); }
+};
+
+// U vectors per lane, `ustride` bytes apart (one workgroup-wide row each): coalesced rows.
+template <int W, int U>
+__device__ __forceinline__ void load_rows(typename VecOf<W>::type (&x)[U], __amdgpu_buffer_rsrc_t r,
+                                          uint32_t lane_off, uint32_t ustride) {
+#pragma unroll
+    for (int u = 0; u < U; u++) x[u] = BufIO<W>::ld(r, lane_off, u * ustride);
+}
+template <int W, int U>
+__device__ __forceinline__ void store_rows(const typename VecOf<W>::type (&x)[U], __amdgpu_buffer_rsrc_t r,
+                                           uint32_t lane_off, uint32_t ustride) {
+#pragma unroll
+    for (int u = 0; u < U; u++) BufIO<W>::st(x[u], r, lane_off, u * ustride);
 }
 
 // ---- accumulators: how one vector of W bytes is widened, summed and narrowed per dtype
@@ -118,50 +160,51 @@ template <int W> struct Acc<SCCL_F16, W> {           // binary16 in memory, bina
     }
 };
 
-// NS sources of a reduce group (NS is a compile-time batch size): issue every load, then add in
-// order.  In the FIRST batch the accumulators start from the destination's value d0, whose load
-// was issued just before this batch's loads, so all of them are in flight together.
-template <int DT, int W, int U, int NS, bool FULL, bool FIRST>
+// What every op of one work item shares.
+struct Tile {
+    int64_t item_off;        // byte offset of the tile in every rank buffer
+    uint32_t bytes;          // bytes of the tile that exist (the last tile of a chunk may be short)
+    uint32_t lane_off;       // this lane's byte offset in a row
+    uint32_t ustride;        // bytes per row
+};
+
+// NS sources of a reduce group (NS is a compile-time batch size): all scalar work (operand words,
+// pointers, descriptors) first, then every load back to back, then the adds in order.  In the
+// FIRST batch the accumulators start from the destination's value d0, whose load was issued just
+// before this batch's loads, so all of them are in flight together.
+template <int DT, int W, int U, int NS, bool FIRST>
 __device__ __forceinline__ void reduce_batch(Acc<DT, W> (&acc)[U], const typename VecOf<W>::type (&d0)[U],
-                                             const ExecArgs& a, table_ptr srcs,
-                                             int64_t off, int64_t stride, const bool (&ok)[U]) {
+                                             const ExecArgs& a, table_ptr srcs, const Tile& t) {
     typedef typename VecOf<W>::type V;
     V x[NS][U];
+    __amdgpu_buffer_rsrc_t r[NS];
 #pragma unroll
-    for (int j = 0; j < NS; j++) {
-        const int32_t w = srcs[j];
-        const char* p = a.bufs[w & OPERAND_RANK_MASK] + off;
+    for (int j = 0; j < NS; j++) r[j] = tile_rsrc(a.bufs[srcs[j]] + t.item_off, t.bytes);
 #pragma unroll
-        for (int u = 0; u < U; u++)
-            if (FULL || ok[u]) x[j][u] = load_vec<V>(p + u * stride);
-    }
+    for (int j = 0; j < NS; j++) load_rows<W, U>(x[j], r[j], t.lane_off, t.ustride);
     if (FIRST) {
 #pragma unroll
-        for (int u = 0; u < U; u++)
-            if (FULL || ok[u]) acc[u].init(d0[u]);
+        for (int u = 0; u < U; u++) acc[u].init(d0[u]);
     }
 #pragma unroll
     for (int j = 0; j < NS; j++)
 #pragma unroll
-        for (int u = 0; u < U; u++)
-            if (FULL || ok[u]) acc[u].add(x[j][u]);
+        for (int u = 0; u < U; u++) acc[u].add(x[j][u]);
 }
 
-template <int DT, int W, int U, bool FULL, bool FIRST>
+template <int DT, int W, int U, bool FIRST>
 __device__ __forceinline__ void reduce_some(int32_t n, Acc<DT, W> (&acc)[U], const typename VecOf<W>::type (&d0)[U],
-                                            const ExecArgs& a, table_ptr srcs,
-                                            int64_t off, int64_t stride, const bool (&ok)[U]) {
+                                            const ExecArgs& a, table_ptr srcs, const Tile& t) {
     switch (n) {
-        case 4:  reduce_batch<DT, W, U, 4, FULL, FIRST>(acc, d0, a, srcs, off, stride, ok); break;
-        case 3:  reduce_batch<DT, W, U, 3, FULL, FIRST>(acc, d0, a, srcs, off, stride, ok); break;
-        case 2:  reduce_batch<DT, W, U, 2, FULL, FIRST>(acc, d0, a, srcs, off, stride, ok); break;
-        default: reduce_batch<DT, W, U, 1, FULL, FIRST>(acc, d0, a, srcs, off, stride, ok); break;
+        case 4:  reduce_batch<DT, W, U, 4, FIRST>(acc, d0, a, srcs, t); break;
+        case 3:  reduce_batch<DT, W, U, 3, FIRST>(acc, d0, a, srcs, t); break;
+        case 2:  reduce_batch<DT, W, U, 2, FIRST>(acc, d0, a, srcs, t); break;
+        default: reduce_batch<DT, W, U, 1, FIRST>(acc, d0, a, srcs, t); break;
     }
 }
 
-template <int DT, int W, int U, bool FULL>
-__device__ __forceinline__ void run_ops(const ExecArgs& a, table_ptr op, table_ptr end,
-                                        int64_t off, int64_t stride, const bool (&ok)[U]) {
+template <int DT, int W, int U>
+__device__ __forceinline__ void run_ops(const ExecArgs& a, table_ptr op, table_ptr end, const Tile& t) {
     typedef typename VecOf<W>::type V;
     while (op < end) {
         const int32_t hdr = op[0];
@@ -169,40 +212,33 @@ __device__ __forceinline__ void run_ops(const ExecArgs& a, table_ptr op, table_p
         if ((hdr & OP_KIND_REDUCE) == 0) {
             // copy group: one read, k writes
             const int32_t ws = op[1];
-            const char* ps = a.bufs[ws & OPERAND_RANK_MASK] + off;
             V x[U];
-#pragma unroll
-            for (int u = 0; u < U; u++)
-                if (FULL || ok[u]) x[u] = load_vec<V>(ps + u * stride);
+            load_rows<W, U>(x, tile_rsrc(a.bufs[ws] + t.item_off, t.bytes), t.lane_off, t.ustride);
             for (int32_t d = 0; d < k; d++) {
                 const int32_t wd = op[2 + d];
-                char* pd = a.bufs[wd & OPERAND_RANK_MASK] + off;
-#pragma unroll
-                for (int u = 0; u < U; u++)
-                    if (FULL || ok[u]) store_vec<V>(pd + u * stride, x[u]);
+                store_rows<W, U>(x, tile_rsrc(a.bufs[wd] + t.item_off, t.bytes), t.lane_off, t.ustride);
             }
         } else {
             // reduce group: destination first, then the k sources in schedule order
             const int32_t wd = op[1];
-            char* pd = a.bufs[wd & OPERAND_RANK_MASK] + off;
+            const __amdgpu_buffer_rsrc_t rd = tile_rsrc(a.bufs[wd] + t.item_off, t.bytes);
             Acc<DT, W> acc[U];
             V d0[U];
-#pragma unroll
-            for (int u = 0; u < U; u++)
-                if (FULL || ok[u]) d0[u] = load_vec<V>(pd + u * stride);
+            load_rows<W, U>(d0, rd, t.lane_off, t.ustride);
             table_ptr srcs = op + 2;
             int32_t left = k;                                  // k >= 1
             int32_t n = left < 4 ? left : 4;
-            reduce_some<DT, W, U, FULL, true>(n, acc, d0, a, srcs, off, stride, ok);
+            reduce_some<DT, W, U, true>(n, acc, d0, a, srcs, t);
             srcs += n; left -= n;
             while (left > 0) {                                 // fan-in above 4: further batches, still in order
                 n = left < 4 ? left : 4;
-                reduce_some<DT, W, U, FULL, false>(n, acc, d0, a, srcs, off, stride, ok);
+                reduce_some<DT, W, U, false>(n, acc, d0, a, srcs, t);
                 srcs += n; left -= n;
             }
+            V out[U];
 #pragma unroll
-            for (int u = 0; u < U; u++)
-                if (FULL || ok[u]) store_vec<V>(pd + u * stride, acc[u].template done<V>());
+            for (int u = 0; u < U; u++) out[u] = acc[u].template done<V>();
+            store_rows<W, U>(out, rd, t.lane_off, t.ustride);
         }
         op += 2 + k;
     }
@@ -211,23 +247,19 @@ __device__ __forceinline__ void run_ops(const ExecArgs& a, table_ptr op, table_p
 // Persistent kernel: workgroup b takes work items b, b + grid, ... ; a work item is (chunk, tile).
 template <int DT, int W, int U>
 __global__ void __launch_bounds__(256) sccl_exec_kernel(const ExecArgs a) {
-    const int64_t tile_vecs = (int64_t)blockDim.x * U;
-    const int64_t stride = (int64_t)blockDim.x * W;           // bytes between a lane's consecutive vectors
+    const uint32_t tile_bytes = blockDim.x * U * W;
+    Tile t;
+    t.lane_off = threadIdx.x * W;
+    t.ustride = blockDim.x * W;
+    table_ptr offs = (table_ptr)a.chunk_off;
     for (int64_t item = blockIdx.x; item < a.num_items; item += gridDim.x) {
         const int32_t c = (int32_t)(item / a.tiles_per_chunk);
         const int32_t tile = (int32_t)(item - (int64_t)c * a.tiles_per_chunk);
-        const int64_t v0 = (int64_t)tile * tile_vecs + threadIdx.x;
-        const int64_t off = ((int64_t)c * a.vecs_per_chunk + v0) * W;
-        table_ptr offs = (table_ptr)a.chunk_off;
-        table_ptr op = (table_ptr)a.prog + offs[c];
-        table_ptr end = (table_ptr)a.prog + offs[c + 1];
-        bool ok[U];
-#pragma unroll
-        for (int u = 0; u < U; u++) ok[u] = v0 + (int64_t)u * blockDim.x < a.vecs_per_chunk;
-        if ((int64_t)(tile + 1) * tile_vecs <= a.vecs_per_chunk)
-            run_ops<DT, W, U, true>(a, op, end, off, stride, ok);
-        else
-            run_ops<DT, W, U, false>(a, op, end, off, stride, ok);
+        const int64_t in_chunk = (int64_t)tile * tile_bytes;
+        const int64_t rest = a.chunk_bytes - in_chunk;
+        t.item_off = (int64_t)c * a.chunk_bytes + in_chunk;
+        t.bytes = rest < (int64_t)tile_bytes ? (uint32_t)rest : tile_bytes;
+        run_ops<DT, W, U>(a, (table_ptr)a.prog + offs[c], (table_ptr)a.prog + offs[c + 1], t);
     }
 }
 
@@ -243,7 +275,8 @@ kernel_fn pick_u(int U) {
     switch (U) {
         case 1: return sccl_exec_kernel<DT, W, 1>;
         case 2: return sccl_exec_kernel<DT, W, 2>;
-        default: return sccl_exec_kernel<DT, W, 4>;
+        case 4: return sccl_exec_kernel<DT, W, 4>;
+        default: return sccl_exec_kernel<DT, W, 8>;
     }
 }
 
@@ -302,15 +335,11 @@ sccl_status_t sccl_plan_create_ex(const sccl_topology_t* topology, const sccl_co
                     hipMalloc((void**)&plan->d_chunk_off, ob) == hipSuccess &&
                     (pb == 0 || hipMemcpy(plan->d_prog, plan->prog.data(), pb, hipMemcpyHostToDevice) == hipSuccess) &&
                     hipMemcpy(plan->d_chunk_off, plan->chunk_off.data(), ob, hipMemcpyHostToDevice) == hipSuccess;
-        int per_cu = 0;
-        if (good) {
-            kernel_fn fn = pick_kernel(plan->dtype, plan->vector_bytes, plan->vectors_per_thread);
-            good = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)fn, plan->block_threads, 0) == hipSuccess;
-        }
         if (!good) { sccl_plan_destroy(plan); return SCCL_ERR_DEVICE; }
-        if (per_cu < 1) per_cu = 1;
-        int64_t grid = (int64_t)num_cus * per_cu;
-        if (plan->opts.max_workgroups > 0 && grid > plan->opts.max_workgroups) grid = plan->opts.max_workgroups;
+        // One persistent workgroup per CU: measured best, because fewer tiles in flight means the
+        // values a lane wrote in one step are still in the L2 when it reads them in the next.
+        int64_t grid = num_cus;
+        if (plan->opts.max_workgroups > 0) grid = plan->opts.max_workgroups;
         if (grid > plan->num_items) grid = plan->num_items;
         plan->grid = (int32_t)grid;
         plan->stats.grid_workgroups = plan->grid;
@@ -343,7 +372,7 @@ sccl_status_t sccl_execute(const sccl_plan_t* plan, void* const* rank_buffers, v
     std::memset(&args, 0, sizeof(args));
     args.prog = plan->d_prog;
     args.chunk_off = plan->d_chunk_off;
-    args.vecs_per_chunk = plan->vecs_per_chunk;
+    args.chunk_bytes = plan->stats.chunk_bytes;
     args.num_items = plan->num_items;
     args.tiles_per_chunk = plan->tiles_per_chunk;
     for (int32_t n = 0; n < P; n++) args.bufs[n] = (char*)rank_buffers[n];

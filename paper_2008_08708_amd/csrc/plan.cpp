@@ -46,8 +46,8 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
     if (opts) {
         const int32_t bt = opts->block_threads, vt = opts->vectors_per_thread;
         if (!(bt == 0 || bt == 64 || bt == 128 || bt == 256)) return SCCL_ERR_INVALID_ARG;
-        if (!(vt == 0 || vt == 1 || vt == 2 || vt == 4)) return SCCL_ERR_INVALID_ARG;
-        if (opts->max_workgroups < 0 || opts->cache_hints < 0 || opts->cache_hints > 2) return SCCL_ERR_INVALID_ARG;
+        if (!(vt == 0 || vt == 1 || vt == 2 || vt == 4 || vt == 8)) return SCCL_ERR_INVALID_ARG;
+        if (opts->max_workgroups < 0) return SCCL_ERR_INVALID_ARG;
     }
     int64_t R = 0;
     for (int32_t s = 0; s < S; s++) {
@@ -202,33 +202,15 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
         for (int32_t n = 0; n < P; n++)
             if (coll->post[(size_t)c * P + n] && held[(size_t)c * P + n] != everyone) return SCCL_ERR_POSTCONDITION;
 
-    // ---- emit the program, with streaming marks on accesses whose data is not reused
-    const bool hints = !(opts && opts->cache_hints == 1);
+    // ---- emit the program: per chunk, its groups in step order
     plan->prog.clear();
     plan->chunk_off.assign((size_t)G + 1, 0);
-    struct Access { size_t word; bool reads; };
     for (int32_t c = 0; c < G; c++) {
         plan->chunk_off[(size_t)c] = (int32_t)plan->prog.size();
-        std::vector<std::vector<Access>> by_rank((size_t)P);     // this chunk's accesses per rank, in program order
         for (const Group& g : per_chunk[(size_t)c]) {
-            const size_t base = plan->prog.size();
             plan->prog.push_back(g.kind | ((int32_t)g.others.size() << 8));
             plan->prog.push_back(g.anchor);
             for (int32_t o : g.others) plan->prog.push_back(o);
-            // copy: the anchor (source) is read, the others are written
-            // reduce: the others (sources) are read; the anchor (destination) is read, then written
-            by_rank[(size_t)g.anchor].push_back({base + 1, true});
-            for (size_t j = 0; j < g.others.size(); j++)
-                by_rank[(size_t)g.others[j]].push_back({base + 2 + j, g.kind == OP_KIND_REDUCE});
-        }
-        if (!hints) continue;
-        // An access is marked streaming when the NEXT access of this program to the same (c, n)
-        // does not read it (it is overwritten, or never touched again): nothing gains from
-        // keeping that data in the caches.
-        for (int32_t n = 0; n < P; n++) {
-            const std::vector<Access>& acc = by_rank[(size_t)n];
-            for (size_t i = 0; i < acc.size(); i++)
-                if (i + 1 == acc.size() || !acc[i + 1].reads) plan->prog[acc[i].word] |= OPERAND_STREAM;
         }
     }
     plan->chunk_off[(size_t)G] = (int32_t)plan->prog.size();
@@ -257,16 +239,24 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
     while (W > elem_bytes(coll->dtype) && chunk_bytes % W != 0) W >>= 1;
     plan->vector_bytes = W;
     plan->vecs_per_chunk = chunk_bytes / W;
+    // Work distribution, chosen per chunk size and per schedule (the analogue of choosing the
+    // number of thread blocks per link, paper section 4): one workgroup per CU, and each lane keeps
+    // about 16-20 vector loads in flight per op: an op with fan-in k issues k + 1 loads per
+    // vector, so lanes of a fan-in-4 Allreduce take 4 vectors and lanes of a ring or a copy-only
+    // schedule take 8.  Small chunks shrink the tile until every CU has a work item.
     int32_t bt = (opts && opts->block_threads) ? opts->block_threads : 256;
-    int32_t vt = (opts && opts->vectors_per_thread) ? opts->vectors_per_thread : 2;
+    int32_t vt = (opts && opts->vectors_per_thread) ? opts->vectors_per_thread : 0;
     auto items_for = [&](int32_t b, int32_t v) {
         const int64_t tile = (int64_t)b * v;
         return (int64_t)G * ((plan->vecs_per_chunk + tile - 1) / tile);
     };
-    // small chunks: shrink the tile until there are enough work items to occupy the CUs
-    const int64_t want = (int64_t)8 * (num_cus > 0 ? num_cus : 256);
-    if (!(opts && opts->vectors_per_thread))
+    const int64_t want = (num_cus > 0 ? num_cus : 256);
+    if (vt == 0) {
+        const int32_t loads_per_vector = max_in + 1;
+        vt = 8;
+        while (vt > 1 && vt * loads_per_vector > 20) vt >>= 1;
         while (vt > 1 && items_for(bt, vt) < want) vt >>= 1;
+    }
     if (!(opts && opts->block_threads))
         while (bt > 64 && items_for(bt, vt) < want) bt >>= 1;
     plan->block_threads = bt;

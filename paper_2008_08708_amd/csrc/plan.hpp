@@ -13,12 +13,7 @@
 //   word 0      : kind (bit 0: 0 copy group, 1 reduce group) | count << 8
 //   word 1      : copy: the source rank          reduce: the destination rank
 //   word 2..    : copy: `count` destination ranks reduce: `count` source ranks, in schedule order
-// Each operand word is  rank | flags << 16 ; flag bit 0 (OPERAND_STREAM) marks
-// an access whose data is not touched again by this chunk's program before it
-// is overwritten (or ever): it may bypass the caches' reuse policy.
 constexpr int32_t OP_KIND_REDUCE = 1;
-constexpr int32_t OPERAND_RANK_MASK = 0xffff;
-constexpr int32_t OPERAND_STREAM = 1 << 16;
 
 struct sccl_plan {
     // problem

@@ -57,7 +57,7 @@ class sccl_schedule_t(ctypes.Structure):
 class sccl_options_t(ctypes.Structure):
     _fields_ = [("flags", ctypes.c_uint32), ("block_threads", ctypes.c_int32),
                 ("vectors_per_thread", ctypes.c_int32), ("max_workgroups", ctypes.c_int32),
-                ("cache_hints", ctypes.c_int32)]
+                ("reserved", ctypes.c_int32)]
 
 
 class sccl_stats_t(ctypes.Structure):
@@ -166,7 +166,7 @@ def sccl_plan_create(topology: Topology, collective: Collective, schedule: Sched
                      options: Optional[dict] = None) -> Plan:
     """sccl_plan_create / sccl_plan_create_ex: marshal the three descriptions and return the plan.
 
-    options: dict with any of flags, block_threads, vectors_per_thread, max_workgroups, cache_hints.
+    options: dict with any of flags, block_threads, vectors_per_thread, max_workgroups.
     Raises ScclError carrying the library's status on failure.
     """
     L = lib()

@@ -180,12 +180,25 @@ def test_vector_width_follows_the_chunk_size(dtype, epc, want_w):
     assert name == "SCCL_OK" and st["vector_bytes"] == want_w
 
 
-def test_work_distribution_shrinks_tiles_for_small_chunks():
+def test_work_distribution_follows_chunk_size_and_fan_in():
     topo = tp.torus2d(4, 4)
     ag = col.allgather(16, 4)
     s = gen.greedy_bfs(topo, ag)
     _, tiny = plan_status(topo, ag, s, "f32", 4)                 # 16-byte chunks: one vector each
     assert (tiny["block_threads"], tiny["vectors_per_thread"], tiny["num_work_items"]) == (64, 1, 64)
-    _, big = plan_status(topo, ag, s, "f32", (16 << 20) // 4)
-    assert (big["block_threads"], big["vectors_per_thread"]) == (256, 2)
-    assert big["num_work_items"] == 64 * ((16 << 20) // (256 * 2 * 16))
+    _, big = plan_status(topo, ag, s, "f32", (16 << 20) // 4)     # copy only: 8 vectors per lane
+    assert (big["block_threads"], big["vectors_per_thread"]) == (256, 8)
+    assert big["num_work_items"] == 64 * ((16 << 20) // (256 * 8 * 16))
+    # the headline Allreduce has fan-in 4: five loads per vector, so four vectors per lane
+    ag8 = col.allgather(8, 1)
+    ar, arc = gen.compose_allreduce(gen.greedy_bfs(tp.hcm8(), ag8), ag8)
+    _, head = plan_status(tp.hcm8(), arc, ar, "f32", (32 << 20) // 4)
+    assert head["max_fan_in"] == 4 and (head["block_threads"], head["vectors_per_thread"]) == (256, 4)
+    # a ring has fan-in 1
+    rar, rarc = gen.compose_allreduce(gen.ring_allgather(8, 4), col.allgather(8, 4))
+    _, ring = plan_status(tp.ring(8), rarc, rar, "f16", (16 << 20) // 2)
+    assert ring["max_fan_in"] == 1 and ring["vectors_per_thread"] == 8
+    # every choice still tiles the chunk exactly
+    for st in (tiny, big, head, ring):
+        tile = st["block_threads"] * st["vectors_per_thread"] * st["vector_bytes"]
+        assert st["num_work_items"] == st["num_global_chunks"] * -(-st["chunk_bytes"] // tile)
