@@ -197,3 +197,37 @@ def test_inversion_on_an_asymmetric_topology_uses_reversed_links():
     rc = col.reduce(3, 1, 0)
     assert validate(cyc.reversed(), rc, red).ok
     assert validate(cyc, rc, red).verdict is Verdict.SEND_NO_LINK
+
+
+def test_stored_schedule_files_are_what_the_oracle_writes():
+    import os
+    from oracle import write_schedules as ws
+    from paper_2008_08708_amd import schedule_file
+    for name, (topo, coll, sched) in ws.configurations().items():
+        path = os.path.join(ws.OUT, name + ".txt")
+        assert open(path).read() == ws.render(name, topo, coll, sched), name
+        sf = schedule_file.load(name)                     # and the reader gives back the same plan
+        assert (sf.num_nodes, sf.num_chunks, sf.rounds) == (coll.num_nodes, coll.num_chunks, sched.rounds)
+        assert (sf.sends == sched.sends).all() and (sf.pre == coll.pre).all() and (sf.post == coll.post).all()
+        assert sorted((sorted(L), b) for L, b in sf.bw) == sorted((sorted(L), b) for L, b in topo.bw)
+        assert sf.combining == coll.combining
+
+
+def test_configuration_schedules_have_the_stated_shape():
+    from oracle import write_schedules as ws
+    cfg = ws.configurations()
+    t, c, s = cfg["cfg1_allgather_ring4"]
+    assert (s.num_steps, s.num_rounds, s.sends.shape[0]) == (2, 2, 12)
+    t, c, s = cfg["cfg2_allgather_hcm8"]
+    assert (c.num_chunks, s.sends.shape[0]) == (16, 112) and s.num_steps >= 3
+    t, c, s = cfg["cfg3_allreduce_hcm8"]
+    assert (c.num_chunks, s.num_steps, s.sends.shape[0]) == (8, 4, 112)
+    assert (s.sends[:, 4] == REDUCE).sum() == 56
+    t, c, s = cfg["cfg4_allreduce_ring8"]
+    assert (c.num_chunks, s.num_steps, s.rounds) == (32, 14, [2] * 14)
+    t, c, s = cfg["cfg4b_allreduce_ring8_c2"]
+    assert s.csr(c.num_chunks) == (16, 14, 14)             # the paper's row for the 8-ring machine
+    t, c, s = cfg["cfg5_allreduce_torus4x4"]
+    assert (c.num_chunks, s.num_steps, s.sends.shape[0]) == (64, 30, 1920)
+    for name, (t, c, s) in cfg.items():
+        assert validate(t, c, s).ok
