@@ -7,8 +7,8 @@ graph (configuration 3).  Every step is timed with HIP events recorded on the st
 is launched on; the in-place buffers are restored from a pristine device copy between steps,
 outside the timed windows.
 
-Prints ONE JSON line on stdout.  `--report` additionally times the other configurations and
-writes a table under gpurun_out/.
+Prints ONE JSON line on stdout.  `--report FILE` additionally times the other configurations and
+writes a markdown table to FILE.
 """
 import argparse
 import json
@@ -155,7 +155,7 @@ def main():
     ap.add_argument("--vectors-per-thread", type=int, default=0)
     ap.add_argument("--max-workgroups", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--report", action="store_true", help="also time the other configurations; table under gpurun_out/")
+    ap.add_argument("--report", default="", metavar="FILE", help="also time the other configurations; markdown table to FILE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build executes P virtual ranks on ONE GPU; --gpus N with N > 1 is not supported "
@@ -232,8 +232,8 @@ def main():
             print(f"[report] {label}: {med * 1e3:.1f} us median, {rows[-1][8]:.1f} GB/s", file=sys.stderr, flush=True)
             del r
             torch.cuda.empty_cache()
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "bench_report.md"), "w") as f:
+        os.makedirs(os.path.dirname(os.path.abspath(args.report)), exist_ok=True)
+        with open(args.report, "w") as f:
             f.write("| workload | P | bytes/rank | chunk bytes | S | bytes_min | median us | min us | effective GB/s | % of 8 TB/s | block | vec/lane | grid |\n")
             f.write("|---|---|---|---|---|---|---|---|---|---|---|---|---|\n")
             for r in rows:
