@@ -215,8 +215,9 @@ def test_device_generator_matches_host_generator():
 
 def test_copy_kernel():
     import torch
-    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
-    dst = torch.zeros_like(src)
-    sccl.sccl_copy_kernel(dst, src, src.numel() * 4)
-    torch.cuda.synchronize()
-    assert torch.equal(src, dst)
+    for n in ((1 << 20) + 4 * 37, 4 * 5, 8192 * 3):          # whole tiles plus a tail; a tail only; tiles only
+        src = torch.arange(n, dtype=torch.int32, device="cuda")
+        dst = torch.zeros_like(src)
+        sccl.sccl_copy_kernel(dst, src, n * 4)
+        torch.cuda.synchronize()
+        assert torch.equal(src, dst)
