@@ -173,3 +173,99 @@ def recursive_doubling_ring4() -> Schedule:
              (0, 0, 3, 1), (1, 0, 3, 1), (2, 3, 0, 1), (3, 3, 0, 1),
              (0, 1, 2, 1), (1, 1, 2, 1), (2, 2, 1, 1), (3, 2, 1, 1)]
     return Schedule([1, 2], np.array([list(t) + [COPY] for t in sends], dtype=np.int32))
+
+
+def greedy_route(topo: Topology, coll: Collective, rounds: Optional[Sequence[int]] = None,
+                 max_steps: int = 1000) -> Schedule:
+    """Greedy shortest-path schedule for ANY non-combining collective (Gather, Scatter, Broadcast, Alltoall, ...).
+
+    For every chunk a tree is fixed first: breadth-first from the nodes that hold it (pre) over the
+    usable links; a node is *wanted* if it is in post or lies on the tree path to a node in post.  A
+    wanted node's parent is, among its breadth-first predecessors, the one with the fewest children
+    assigned so far over all chunks on that link (spreads an Alltoall over parallel shortest paths;
+    lowest id on ties).  Every wanted node receives the chunk exactly once, from its parent (the
+    one-receive rule C3 and the ordering rule C4 of section 3.4 hold by construction).
+
+    Then the sends are packed into steps: in step s every constraint (L, b) has budget b * r_s; the
+    pending sends whose parent already holds the chunk are served deepest-subtree-first (the longest
+    remaining path below the receiver), ties by (chunk, receiver).
+    """
+    P, G = coll.num_nodes, coll.num_chunks
+    if coll.combining:
+        raise GenerationError("greedy_route handles non-combining collectives")
+    links = topo.edges()
+    in_nb: Dict[int, List[int]] = {n: [s for (s, d) in links if d == n] for n in range(P)}
+    out_nb: Dict[int, List[int]] = {n: [d for (s, d) in links if s == n] for n in range(P)}
+    constraints_of: Dict[Tuple[int, int], List[int]] = {
+        e: [i for i, (L, b) in enumerate(topo.bw) if e in L] for e in links}
+    link_load: Dict[Tuple[int, int], int] = {e: 0 for e in links}
+
+    parent: Dict[Tuple[int, int], int] = {}          # (c, n) -> node it receives c from
+    height: Dict[Tuple[int, int], int] = {}          # longest path of wanted nodes below (c, n)
+    for c in range(G):
+        holders = [n for n in range(P) if coll.pre[c, n]]
+        targets = [n for n in range(P) if coll.post[c, n] and not coll.pre[c, n]]
+        if not targets:
+            continue
+        if not holders:
+            raise GenerationError(f"chunk {c} is nowhere in pre")
+        dist = {n: 0 for n in holders}
+        frontier = list(holders)
+        while frontier:
+            nxt = []
+            for u in frontier:
+                for v in out_nb[u]:
+                    if v not in dist:
+                        dist[v] = dist[u] + 1
+                        nxt.append(v)
+            frontier = nxt
+        wanted = set()
+        # farthest targets first, so that shared prefixes are reused by nearer ones
+        for t in sorted(targets, key=lambda n: (-dist.get(n, -1), n)):
+            if t not in dist:
+                raise GenerationError(f"chunk {c} cannot reach node {t}")
+            n = t
+            while dist[n] > 0 and n not in wanted:
+                wanted.add(n)
+                preds = [m for m in in_nb[n] if dist.get(m, -1) == dist[n] - 1]
+                # prefer a predecessor already on the tree, then the least loaded link
+                best = min(preds, key=lambda m: (0 if (m in wanted or dist[m] == 0) else 1, link_load[(m, n)], m))
+                parent[(c, n)] = best
+                link_load[(best, n)] += 1
+                n = best
+        for n in sorted(wanted, key=lambda n: -dist[n]):
+            height.setdefault((c, n), 0)
+            p = parent[(c, n)]
+            if dist[p] > 0:
+                height[(c, p)] = max(height.get((c, p), 0), height[(c, n)] + 1)
+
+    have = coll.pre.astype(bool).copy()
+    pending = set(parent.keys())
+    sends: List[Tuple[int, int, int, int, int]] = []
+    rounds_out: List[int] = []
+    s = 0
+    while pending:
+        if s >= max_steps:
+            raise GenerationError("step limit reached")
+        r_s = int(rounds[s]) if rounds is not None and s < len(rounds) else 1
+        budget = [b * r_s for (L, b) in topo.bw]
+        ready = sorted((key for key in pending if have[key[0], parent[key]]),
+                       key=lambda key: (-height[key], key[0], key[1]))
+        got = []
+        for (c, n) in ready:
+            e = (parent[(c, n)], n)
+            if all(budget[i] > 0 for i in constraints_of[e]):
+                for i in constraints_of[e]:
+                    budget[i] -= 1
+                sends.append((c, e[0], n, s, COPY))
+                got.append((c, n))
+        if not got:
+            raise GenerationError(f"step {s} could not send anything")
+        for key in got:
+            have[key] = True
+            pending.discard(key)
+        rounds_out.append(r_s)
+        s += 1
+    if not rounds_out:
+        rounds_out = [1]
+    return Schedule(rounds_out, np.array(sends, dtype=np.int32).reshape(-1, 5))

@@ -1,0 +1,63 @@
+"""GPU parity for the other collectives of Table 2 and Reduce: same library, same kernel, other (pre, post)."""
+import numpy as np
+import pytest
+
+from gpu_util import assert_same_bits, bits, run_both
+from oracle import collective as col
+from oracle import generate as gen
+from oracle import topology as tp
+from oracle.validate import validate
+from paper_2008_08708_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+TOPOS = [tp.ring(8), tp.hcm8(), tp.dgx1(), tp.torus2d(4, 4)]
+
+
+def poisoned(coll, dtype, dist, seed, epc):
+    P, G = coll.num_nodes, coll.num_chunks
+    bufs = [inputs.generate(dist, dtype, seed, n, 0, G * epc) for n in range(P)]
+    for n in range(P):
+        for c in range(G):
+            if not coll.pre[c, n]:
+                inputs.poison(bufs[n], c * epc, (c + 1) * epc)
+    return bufs
+
+
+@pytest.mark.parametrize("topo", TOPOS, ids=[t.name for t in TOPOS])
+@pytest.mark.parametrize("which", ["broadcast", "gather", "scatter", "alltoall"])
+def test_non_combining_collectives(topo, which):
+    P = topo.num_nodes
+    coll = {"broadcast": lambda: col.broadcast(P, 3, 1), "gather": lambda: col.gather(P, 2, P - 1),
+            "scatter": lambda: col.scatter(P, 2 * P, 0), "alltoall": lambda: col.alltoall(P, P)}[which]()
+    s = gen.greedy_route(topo, coll)
+    assert validate(topo, coll, s).ok
+    epc = 2048 + 4 * 21
+    bufs = poisoned(coll, "f32", "uniform", 41, epc)
+    want, got = run_both(topo, coll, s, "f32", bufs, epc, label=f"{which}-{topo.name}")
+    assert_same_bits(want, got)
+    for c in range(coll.num_chunks):                      # closed form on the post-condition
+        owner = int(np.nonzero(coll.pre[c])[0][0])
+        for m in range(P):
+            if coll.post[c, m]:
+                assert (bits(got[m][c * epc:(c + 1) * epc]) == bits(bufs[owner][c * epc:(c + 1) * epc])).all()
+
+
+@pytest.mark.parametrize("topo", TOPOS, ids=[t.name for t in TOPOS])
+@pytest.mark.parametrize("dtype,dist", [("f32", "uniform"), ("f16", "normal"), ("i32", "u32")])
+def test_reduce_to_a_root(topo, dtype, dist):
+    P, C, root = topo.num_nodes, 3, 2
+    bc = col.broadcast(P, C, root)
+    red = gen.invert(gen.greedy_route(topo, bc), bc)
+    rc = col.reduce(P, C, root)
+    rtopo = topo.reversed()
+    assert validate(rtopo, rc, red).ok
+    epc = 1024 + 8 * 3
+    bufs = [inputs.generate(dist, dtype, 43, n, 0, C * epc) for n in range(P)]
+    want, got = run_both(rtopo, rc, red, dtype, bufs, epc, label=f"reduce-{topo.name}")
+    assert_same_bits(want, got)
+    if dtype == "i32":
+        direct = np.zeros(C * epc, dtype=np.uint32)
+        for b in bufs:
+            direct = direct + b.view(np.uint32)
+        assert (got[root].view(np.uint32) == direct).all()

@@ -202,3 +202,18 @@ def test_work_distribution_follows_chunk_size_and_fan_in():
     for st in (tiny, big, head, ring):
         tile = st["block_threads"] * st["vectors_per_thread"] * st["vector_bytes"]
         assert st["num_work_items"] == st["num_global_chunks"] * -(-st["chunk_bytes"] // tile)
+
+
+def test_other_collectives_are_accepted():
+    for topo in (tp.ring(8), tp.hcm8(), tp.torus2d(4, 4)):
+        P = topo.num_nodes
+        for coll in (col.broadcast(P, 3, 1), col.gather(P, 2, P - 1), col.scatter(P, 2 * P, 0), col.alltoall(P, P)):
+            s = gen.greedy_route(topo, coll)
+            assert validate(topo, coll, s).ok
+            name, st = plan_status(topo, coll, s, "f32", 64)
+            assert name == "SCCL_OK" and st["num_reduce_groups"] == 0
+            assert st["bytes_min"] == ex.algorithmic_bytes(s, 256)[0]
+        bc = col.broadcast(P, 2, 0)
+        red = gen.invert(gen.greedy_route(topo, bc), bc)
+        name, st = plan_status(topo.reversed(), col.reduce(P, 2, 0), red, "f16", 64)
+        assert name == "SCCL_OK" and st["num_copy_groups"] == 0
