@@ -175,6 +175,19 @@ sccl_status_t sccl_plan_create_ex(const sccl_topology_t* topology, const sccl_co
  */
 sccl_status_t sccl_execute(const sccl_plan_t* plan, void* const* rank_buffers, void* stream);
 
+/*
+ * The two other lowerings the paper compares its fused kernel with (section 4, "single and multiple
+ * kernels", and section 5.5): same arguments, same checks and same results as sccl_execute.
+ *
+ * sccl_execute_stepwise enqueues ONE kernel per step (the kernel boundary is the global
+ * synchronisation between steps); each kernel fuses the copy and reduce groups of its step.
+ *
+ * sccl_execute_memcpy enqueues one device-to-device hipMemcpyAsync per COPY send, in step order
+ * (the copy-engine lowering).  Only for plans without REDUCE sends: otherwise SCCL_ERR_INVALID_ARG.
+ */
+sccl_status_t sccl_execute_stepwise(const sccl_plan_t* plan, void* const* rank_buffers, void* stream);
+sccl_status_t sccl_execute_memcpy(const sccl_plan_t* plan, void* const* rank_buffers, void* stream);
+
 /* S, R, k, group counts, algorithmic byte counts and the launch shape. */
 sccl_status_t sccl_plan_stats(const sccl_plan_t* plan, sccl_stats_t* out_stats);
 

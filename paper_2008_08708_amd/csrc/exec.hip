@@ -172,9 +172,9 @@ struct Tile {
 // pointers, descriptors) first, then every load back to back, then the adds in order.  In the
 // FIRST batch the accumulators start from the destination's value d0, whose load was issued just
 // before this batch's loads, so all of them are in flight together.
-template <int DT, int W, int U, int NS, bool FIRST>
+template <int DT, int W, int U, int NS, bool FIRST, class Args>
 __device__ __forceinline__ void reduce_batch(Acc<DT, W> (&acc)[U], const typename VecOf<W>::type (&d0)[U],
-                                             const ExecArgs& a, table_ptr srcs, const Tile& t) {
+                                             const Args& a, table_ptr srcs, const Tile& t) {
     typedef typename VecOf<W>::type V;
     V x[NS][U];
     __amdgpu_buffer_rsrc_t r[NS];
@@ -192,9 +192,9 @@ __device__ __forceinline__ void reduce_batch(Acc<DT, W> (&acc)[U], const typenam
         for (int u = 0; u < U; u++) acc[u].add(x[j][u]);
 }
 
-template <int DT, int W, int U, bool FIRST>
+template <int DT, int W, int U, bool FIRST, class Args>
 __device__ __forceinline__ void reduce_some(int32_t n, Acc<DT, W> (&acc)[U], const typename VecOf<W>::type (&d0)[U],
-                                            const ExecArgs& a, table_ptr srcs, const Tile& t) {
+                                            const Args& a, table_ptr srcs, const Tile& t) {
     switch (n) {
         case 4:  reduce_batch<DT, W, U, 4, FIRST>(acc, d0, a, srcs, t); break;
         case 3:  reduce_batch<DT, W, U, 3, FIRST>(acc, d0, a, srcs, t); break;
@@ -203,45 +203,44 @@ __device__ __forceinline__ void reduce_some(int32_t n, Acc<DT, W> (&acc)[U], con
     }
 }
 
-template <int DT, int W, int U>
-__device__ __forceinline__ void run_ops(const ExecArgs& a, table_ptr op, table_ptr end, const Tile& t) {
+// One op on one tile: op points at  header | anchor rank | other ranks...  ; returns the word count.
+template <int DT, int W, int U, class Args>
+__device__ __forceinline__ int32_t do_op(const Args& a, table_ptr op, const Tile& t) {
     typedef typename VecOf<W>::type V;
-    while (op < end) {
-        const int32_t hdr = op[0];
-        const int32_t k = hdr >> 8;
-        if ((hdr & OP_KIND_REDUCE) == 0) {
-            // copy group: one read, k writes
-            const int32_t ws = op[1];
-            V x[U];
-            load_rows<W, U>(x, tile_rsrc(a.bufs[ws] + t.item_off, t.bytes), t.lane_off, t.ustride);
-            for (int32_t d = 0; d < k; d++) {
-                const int32_t wd = op[2 + d];
-                store_rows<W, U>(x, tile_rsrc(a.bufs[wd] + t.item_off, t.bytes), t.lane_off, t.ustride);
-            }
-        } else {
-            // reduce group: destination first, then the k sources in schedule order
-            const int32_t wd = op[1];
-            const __amdgpu_buffer_rsrc_t rd = tile_rsrc(a.bufs[wd] + t.item_off, t.bytes);
-            Acc<DT, W> acc[U];
-            V d0[U];
-            load_rows<W, U>(d0, rd, t.lane_off, t.ustride);
-            table_ptr srcs = op + 2;
-            int32_t left = k;                                  // k >= 1
-            int32_t n = left < 4 ? left : 4;
-            reduce_some<DT, W, U, true>(n, acc, d0, a, srcs, t);
-            srcs += n; left -= n;
-            while (left > 0) {                                 // fan-in above 4: further batches, still in order
-                n = left < 4 ? left : 4;
-                reduce_some<DT, W, U, false>(n, acc, d0, a, srcs, t);
-                srcs += n; left -= n;
-            }
-            V out[U];
-#pragma unroll
-            for (int u = 0; u < U; u++) out[u] = acc[u].template done<V>();
-            store_rows<W, U>(out, rd, t.lane_off, t.ustride);
+    const int32_t hdr = op[0];
+    const int32_t k = hdr >> 8;
+    if ((hdr & OP_KIND_REDUCE) == 0) {
+        // copy group: one read, k writes
+        const int32_t ws = op[1];
+        V x[U];
+        load_rows<W, U>(x, tile_rsrc(a.bufs[ws] + t.item_off, t.bytes), t.lane_off, t.ustride);
+        for (int32_t d = 0; d < k; d++) {
+            const int32_t wd = op[2 + d];
+            store_rows<W, U>(x, tile_rsrc(a.bufs[wd] + t.item_off, t.bytes), t.lane_off, t.ustride);
         }
-        op += 2 + k;
+    } else {
+        // reduce group: destination first, then the k sources in schedule order
+        const int32_t wd = op[1];
+        const __amdgpu_buffer_rsrc_t rd = tile_rsrc(a.bufs[wd] + t.item_off, t.bytes);
+        Acc<DT, W> acc[U];
+        V d0[U];
+        load_rows<W, U>(d0, rd, t.lane_off, t.ustride);
+        table_ptr srcs = op + 2;
+        int32_t left = k;                                  // k >= 1
+        int32_t n = left < 4 ? left : 4;
+        reduce_some<DT, W, U, true>(n, acc, d0, a, srcs, t);
+        srcs += n; left -= n;
+        while (left > 0) {                                 // fan-in above 4: further batches, still in order
+            n = left < 4 ? left : 4;
+            reduce_some<DT, W, U, false>(n, acc, d0, a, srcs, t);
+            srcs += n; left -= n;
+        }
+        V out[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) out[u] = acc[u].template done<V>();
+        store_rows<W, U>(out, rd, t.lane_off, t.ustride);
     }
+    return 2 + k;
 }
 
 // Persistent kernel: workgroup b takes work items b, b + grid, ... ; a work item is (chunk, tile).
@@ -259,7 +258,42 @@ __global__ void __launch_bounds__(256) sccl_exec_kernel(const ExecArgs a) {
         const int64_t rest = a.chunk_bytes - in_chunk;
         t.item_off = (int64_t)c * a.chunk_bytes + in_chunk;
         t.bytes = rest < (int64_t)tile_bytes ? (uint32_t)rest : tile_bytes;
-        run_ops<DT, W, U>(a, (table_ptr)a.prog + offs[c], (table_ptr)a.prog + offs[c + 1], t);
+        table_ptr op = (table_ptr)a.prog + offs[c];
+        table_ptr end = (table_ptr)a.prog + offs[c + 1];
+        while (op < end) op += do_op<DT, W, U>(a, op, t);
+    }
+}
+
+// The step-per-launch lowering (paper section 4, "multiple kernels, one per step"): one launch
+// executes the groups of ONE step; a work item is (group, tile).  The kernel boundary is the
+// global synchronisation between steps.  Kept as a comparator for the fused kernel above.
+struct StepArgs {
+    const int32_t* step_prog;     // per group: chunk | header | anchor | others...
+    const int32_t* group_off;     // word offset of every group, in step order
+    int64_t chunk_bytes;
+    int64_t num_items;            // groups of this step x tiles per chunk
+    int32_t first_group;          // index into group_off of this step's first group
+    int32_t tiles_per_chunk;
+    char* bufs[SCCL_MAX_RANKS];
+};
+
+template <int DT, int W, int U>
+__global__ void __launch_bounds__(256) sccl_step_kernel(const StepArgs a) {
+    const uint32_t tile_bytes = blockDim.x * U * W;
+    Tile t;
+    t.lane_off = threadIdx.x * W;
+    t.ustride = blockDim.x * W;
+    table_ptr goff = (table_ptr)a.group_off;
+    for (int64_t item = blockIdx.x; item < a.num_items; item += gridDim.x) {
+        const int32_t g = (int32_t)(item / a.tiles_per_chunk);
+        const int32_t tile = (int32_t)(item - (int64_t)g * a.tiles_per_chunk);
+        table_ptr op = (table_ptr)a.step_prog + goff[a.first_group + g];
+        const int32_t c = op[0];
+        const int64_t in_chunk = (int64_t)tile * tile_bytes;
+        const int64_t rest = a.chunk_bytes - in_chunk;
+        t.item_off = (int64_t)c * a.chunk_bytes + in_chunk;
+        t.bytes = rest < (int64_t)tile_bytes ? (uint32_t)rest : tile_bytes;
+        do_op<DT, W, U>(a, op + 1, t);
     }
 }
 
@@ -281,6 +315,34 @@ __global__ void __launch_bounds__(256) copy16_kernel(u32x4* __restrict__ dst, co
 }
 
 typedef void (*kernel_fn)(const ExecArgs);
+typedef void (*step_kernel_fn)(const StepArgs);
+
+template <int DT, int W>
+step_kernel_fn pick_step_u(int U) {
+    switch (U) {
+        case 1: return sccl_step_kernel<DT, W, 1>;
+        case 2: return sccl_step_kernel<DT, W, 2>;
+        case 4: return sccl_step_kernel<DT, W, 4>;
+        default: return sccl_step_kernel<DT, W, 8>;
+    }
+}
+template <int DT>
+step_kernel_fn pick_step_w(int W, int U) {
+    switch (W) {
+        case 16: return pick_step_u<DT, 16>(U);
+        case 8:  return pick_step_u<DT, 8>(U);
+        default: return pick_step_u<DT, 4>(U);
+    }
+}
+step_kernel_fn pick_step_kernel(sccl_dtype_t dt, int W, int U) {
+    switch (dt) {
+        case SCCL_I32: return pick_step_w<SCCL_I32>(W, U);
+        case SCCL_F32: return pick_step_w<SCCL_F32>(W, U);
+        default:
+            if (W == 2) return pick_step_u<SCCL_F16, 2>(U);
+            return pick_step_w<SCCL_F16>(W, U);
+    }
+}
 
 template <int DT, int W>
 kernel_fn pick_u(int U) {
@@ -342,8 +404,14 @@ sccl_status_t sccl_plan_create_ex(const sccl_topology_t* topology, const sccl_co
     if (st != SCCL_OK) { delete plan; return st; }
     if (!host_only) {
         plan->device = dev;
+        plan->num_cus = num_cus;
         const size_t pb = plan->prog.size() * sizeof(int32_t), ob = plan->chunk_off.size() * sizeof(int32_t);
-        bool good = hipMalloc((void**)&plan->d_prog, pb ? pb : 4) == hipSuccess &&
+        const size_t sb = plan->step_prog.size() * sizeof(int32_t), gb = plan->group_off.size() * sizeof(int32_t);
+        bool good = hipMalloc((void**)&plan->d_step_prog, sb ? sb : 4) == hipSuccess &&
+                    hipMalloc((void**)&plan->d_group_off, gb ? gb : 4) == hipSuccess &&
+                    (sb == 0 || hipMemcpy(plan->d_step_prog, plan->step_prog.data(), sb, hipMemcpyHostToDevice) == hipSuccess) &&
+                    (gb == 0 || hipMemcpy(plan->d_group_off, plan->group_off.data(), gb, hipMemcpyHostToDevice) == hipSuccess) &&
+                    hipMalloc((void**)&plan->d_prog, pb ? pb : 4) == hipSuccess &&
                     hipMalloc((void**)&plan->d_chunk_off, ob) == hipSuccess &&
                     (pb == 0 || hipMemcpy(plan->d_prog, plan->prog.data(), pb, hipMemcpyHostToDevice) == hipSuccess) &&
                     hipMemcpy(plan->d_chunk_off, plan->chunk_off.data(), ob, hipMemcpyHostToDevice) == hipSuccess;
@@ -365,7 +433,7 @@ sccl_status_t sccl_plan_create(const sccl_topology_t* topology, const sccl_colle
     return sccl_plan_create_ex(topology, collective, schedule, nullptr, out_plan);
 }
 
-sccl_status_t sccl_execute(const sccl_plan_t* plan, void* const* rank_buffers, void* stream) {
+static sccl_status_t check_buffers(const sccl_plan_t* plan, void* const* rank_buffers) {
     if (!plan || !rank_buffers) return SCCL_ERR_INVALID_ARG;
     if (plan->device < 0) return SCCL_ERR_DEVICE;
     const int32_t P = plan->P;
@@ -379,6 +447,52 @@ sccl_status_t sccl_execute(const sccl_plan_t* plan, void* const* rank_buffers, v
             const uintptr_t a = (uintptr_t)rank_buffers[n], b = (uintptr_t)rank_buffers[m];
             if (a == b || (a < b ? a + bytes > b : b + bytes > a)) return SCCL_ERR_OVERLAP;
         }
+    return SCCL_OK;
+}
+
+sccl_status_t sccl_execute_stepwise(const sccl_plan_t* plan, void* const* rank_buffers, void* stream) {
+    const sccl_status_t chk = check_buffers(plan, rank_buffers);
+    if (chk != SCCL_OK) return chk;
+    if (plan->num_items == 0 || plan->step_prog.empty()) return SCCL_OK;
+    StepArgs args;
+    std::memset(&args, 0, sizeof(args));
+    args.step_prog = plan->d_step_prog;
+    args.group_off = plan->d_group_off;
+    args.chunk_bytes = plan->stats.chunk_bytes;
+    args.tiles_per_chunk = plan->tiles_per_chunk;
+    for (int32_t n = 0; n < plan->P; n++) args.bufs[n] = (char*)rank_buffers[n];
+    step_kernel_fn fn = pick_step_kernel(plan->dtype, plan->vector_bytes, plan->vectors_per_thread);
+    for (int32_t s = 0; s < plan->S; s++) {
+        const int32_t first = plan->step_first[(size_t)s], count = plan->step_first[(size_t)s + 1] - first;
+        if (count == 0) continue;
+        args.first_group = first;
+        args.num_items = (int64_t)count * plan->tiles_per_chunk;
+        int64_t grid = (int64_t)plan->num_cus * 4;
+        if (grid > args.num_items) grid = args.num_items;
+        hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3((unsigned)plan->block_threads), 0, (hipStream_t)stream, args);
+        if (hipGetLastError() != hipSuccess) return SCCL_ERR_DEVICE;
+    }
+    return SCCL_OK;
+}
+
+sccl_status_t sccl_execute_memcpy(const sccl_plan_t* plan, void* const* rank_buffers, void* stream) {
+    const sccl_status_t chk = check_buffers(plan, rank_buffers);
+    if (chk != SCCL_OK) return chk;
+    if (plan->stats.num_reduce_groups != 0) return SCCL_ERR_INVALID_ARG;     // a copy engine cannot add
+    const size_t cs = (size_t)plan->stats.chunk_bytes;
+    if (cs == 0) return SCCL_OK;
+    for (const auto& t : plan->copy_sends) {
+        char* dst = (char*)rank_buffers[t.dst] + (size_t)t.chunk * cs;
+        const char* src = (const char*)rank_buffers[t.src] + (size_t)t.chunk * cs;
+        if (hipMemcpyAsync(dst, src, cs, hipMemcpyDeviceToDevice, (hipStream_t)stream) != hipSuccess) return SCCL_ERR_DEVICE;
+    }
+    return SCCL_OK;
+}
+
+sccl_status_t sccl_execute(const sccl_plan_t* plan, void* const* rank_buffers, void* stream) {
+    const sccl_status_t chk = check_buffers(plan, rank_buffers);
+    if (chk != SCCL_OK) return chk;
+    const int32_t P = plan->P;
     if (plan->num_items == 0 || plan->prog.empty()) return SCCL_OK;     // nothing to move
     ExecArgs args;
     std::memset(&args, 0, sizeof(args));
@@ -403,6 +517,8 @@ void sccl_plan_destroy(sccl_plan_t* plan) {
     if (!plan) return;
     if (plan->d_prog) (void)hipFree(plan->d_prog);
     if (plan->d_chunk_off) (void)hipFree(plan->d_chunk_off);
+    if (plan->d_step_prog) (void)hipFree(plan->d_step_prog);
+    if (plan->d_group_off) (void)hipFree(plan->d_group_off);
     delete plan;
 }
 

@@ -109,6 +109,8 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
     std::vector<uint8_t> is_read((size_t)G * P, 0), is_written((size_t)G * P, 0);   // 1 copy-written, 2 reduced into
     int64_t n_copy_groups = 0, n_reduce_groups = 0, chunks_min = 0, chunks_unfused = 0;
     int32_t max_in = 0, max_out = 0;
+    plan->step_prog.clear(); plan->group_off.clear(); plan->copy_sends.clear();
+    plan->step_first.assign((size_t)S + 1, 0);
 
     for (int32_t s = 0; s < S; s++) {
         const int64_t lo = first[s], hi = first[(size_t)s + 1];
@@ -191,13 +193,24 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
         for (auto& u : updates) held[u.first] = u.second;
         for (auto& r : reduced) held[r.first] = r.second;
         for (size_t c : consumed) held[c] = 0;
+        plan->step_first[(size_t)s] = (int32_t)plan->group_off.size();
+        for (int64_t q = lo; q < hi; q++) {
+            const sccl_send_t& t = sched->sends[order[(size_t)q]];
+            if (t.op == SCCL_COPY) plan->copy_sends.push_back({t.chunk, t.src, t.dst});
+        }
         for (Group& g : groups) {
             const int32_t k = (int32_t)g.others.size();
+            plan->group_off.push_back((int32_t)plan->step_prog.size());
+            plan->step_prog.push_back(g.chunk);
+            plan->step_prog.push_back(g.kind | (k << 8));
+            plan->step_prog.push_back(g.anchor);
+            for (int32_t o : g.others) plan->step_prog.push_back(o);
             if (g.kind == 0) { n_copy_groups++; chunks_min += 1 + k; max_out = std::max(max_out, k); }
             else             { n_reduce_groups++; chunks_min += k + 2; max_in = std::max(max_in, k); }
             per_chunk[(size_t)g.chunk].push_back(std::move(g));
         }
     }
+    plan->step_first[(size_t)S] = (int32_t)plan->group_off.size();
     for (int32_t c = 0; c < G; c++)
         for (int32_t n = 0; n < P; n++)
             if (coll->post[(size_t)c * P + n] && held[(size_t)c * P + n] != everyone) return SCCL_ERR_POSTCONDITION;

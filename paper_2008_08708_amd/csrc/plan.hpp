@@ -25,6 +25,14 @@ struct sccl_plan {
     // compiled program (host copy)
     std::vector<int32_t> prog;
     std::vector<int32_t> chunk_off;     // G + 1 offsets into prog
+    // the same groups in step order, for the step-per-launch lowering: per group
+    //   chunk | header | anchor | others...
+    std::vector<int32_t> step_prog;
+    std::vector<int32_t> group_off;     // word offset of every group in step_prog, in step order
+    std::vector<int32_t> step_first;    // S + 1 indices into group_off
+    // COPY sends in step order (array order inside a step), for the copy-engine lowering
+    struct CopySend { int32_t chunk, src, dst; };
+    std::vector<CopySend> copy_sends;
     sccl_stats_t stats{};
     sccl_options_t opts{};
     // launch shape
@@ -37,8 +45,11 @@ struct sccl_plan {
     int32_t grid = 0;
     // device side (owned)
     int device = -1;
+    int num_cus = 0;
     int32_t* d_prog = nullptr;
     int32_t* d_chunk_off = nullptr;
+    int32_t* d_step_prog = nullptr;
+    int32_t* d_group_off = nullptr;
 };
 
 // Validates the schedule and fills everything except the device fields and `grid`.

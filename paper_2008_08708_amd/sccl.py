@@ -75,7 +75,8 @@ class sccl_stats_t(ctypes.Structure):
         return {name: getattr(self, name) for name, _ in self._fields_}
 
 
-EXPORTS = ["sccl_plan_create", "sccl_plan_create_ex", "sccl_execute", "sccl_plan_stats", "sccl_plan_destroy",
+EXPORTS = ["sccl_plan_create", "sccl_plan_create_ex", "sccl_execute", "sccl_execute_stepwise", "sccl_execute_memcpy",
+           "sccl_plan_stats", "sccl_plan_destroy",
            "sccl_status_string", "sccl_copy_kernel"]
 
 _lib = None
@@ -102,6 +103,9 @@ def lib() -> ctypes.CDLL:
                                           ctypes.POINTER(ctypes.c_void_p)]
         L.sccl_execute.restype = ctypes.c_int
         L.sccl_execute.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p]
+        for fn in (L.sccl_execute_stepwise, L.sccl_execute_memcpy):
+            fn.restype = ctypes.c_int
+            fn.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p]
         L.sccl_plan_stats.restype = ctypes.c_int
         L.sccl_plan_stats.argtypes = [ctypes.c_void_p, ctypes.POINTER(sccl_stats_t)]
         L.sccl_plan_destroy.restype = None
@@ -207,20 +211,34 @@ def _device_ptr(b) -> int:
     return int(b)
 
 
-def sccl_execute(plan: Plan, rank_buffers: Sequence, stream=None) -> None:
-    """Enqueue the plan on `stream` (a torch stream, a raw hipStream_t value, or None for torch's current stream).
-
-    rank_buffers: P device tensors (or raw device addresses).
-    """
+def _execute(name: str, plan: Plan, rank_buffers: Sequence, stream) -> None:
     if stream is None:
         import torch
         stream = torch.cuda.current_stream().cuda_stream
     elif hasattr(stream, "cuda_stream"):
         stream = stream.cuda_stream
     ptrs = (ctypes.c_void_p * len(rank_buffers))(*[_device_ptr(b) for b in rank_buffers])
-    st = lib().sccl_execute(plan.handle, ptrs, ctypes.c_void_p(int(stream)))
+    st = getattr(lib(), name)(plan.handle, ptrs, ctypes.c_void_p(int(stream)))
     if st != SCCL_OK:
-        raise ScclError(st, "sccl_execute")
+        raise ScclError(st, name)
+
+
+def sccl_execute(plan: Plan, rank_buffers: Sequence, stream=None) -> None:
+    """Enqueue the plan on `stream` (a torch stream, a raw hipStream_t value, or None for torch's current stream).
+
+    rank_buffers: P device tensors (or raw device addresses).
+    """
+    _execute("sccl_execute", plan, rank_buffers, stream)
+
+
+def sccl_execute_stepwise(plan: Plan, rank_buffers: Sequence, stream=None) -> None:
+    """One kernel per step (comparator lowering); same arguments and results as sccl_execute."""
+    _execute("sccl_execute_stepwise", plan, rank_buffers, stream)
+
+
+def sccl_execute_memcpy(plan: Plan, rank_buffers: Sequence, stream=None) -> None:
+    """One device-to-device copy per COPY send (comparator lowering; plans without REDUCE sends only)."""
+    _execute("sccl_execute_memcpy", plan, rank_buffers, stream)
 
 
 def sccl_plan_stats(plan: Plan) -> dict:

@@ -22,15 +22,15 @@ def host_inputs(dist, dtype, seed, P, G, epc, pre=None):
     return bufs
 
 
-def run_both(topo, coll, sched, dtype, bufs, epc, options=None, label=""):
+def run_both(topo, coll, sched, dtype, bufs, epc, options=None, label="", mode="sccl_execute"):
     """Oracle on copies of `bufs`, library on device copies; returns (oracle buffers, gpu buffers as numpy)."""
     import torch
-    print(f"[case] {label} P={coll.num_nodes} G={coll.num_chunks} epc={epc} dtype={dtype} opts={options}", flush=True)
+    print(f"[case] {label} {mode} P={coll.num_nodes} G={coll.num_chunks} epc={epc} dtype={dtype} opts={options}", flush=True)
     want = [b.copy() for b in bufs]
     ex.execute(dtype, coll.num_chunks, epc, sched, want)
     dev = [torch.from_numpy(b.copy()).cuda() for b in bufs]
     plan = sccl.sccl_plan_create(*to_binding(topo, coll, sched, dtype, epc), options=options)
-    sccl.sccl_execute(plan, dev)
+    getattr(sccl, mode)(plan, dev)
     torch.cuda.synchronize()
     got = [d.cpu().numpy() for d in dev]
     sccl.sccl_plan_destroy(plan)
