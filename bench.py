@@ -52,7 +52,7 @@ def make_inputs(wl, sf, device):
     return bufs, epc
 
 
-def time_workload(wl, steps, warmup, options=None, keep=False):
+def time_workload(wl, steps, warmup, options=None, keep=False, mode="sccl_execute"):
     """Returns dict with per-step kernel times (ms) measured by events on the launch stream."""
     import torch
     from paper_2008_08708_amd import schedule_file, sccl
@@ -63,6 +63,7 @@ def time_workload(wl, steps, warmup, options=None, keep=False):
     plan = sccl.sccl_plan_create(*sf.descriptions(wl.dtype, epc), options=options)
     stats = sccl.sccl_plan_stats(plan)
     stream = torch.cuda.current_stream()
+    execute = getattr(sccl, mode)
 
     def restore():
         for w, p in zip(work, pristine):
@@ -70,7 +71,7 @@ def time_workload(wl, steps, warmup, options=None, keep=False):
 
     for _ in range(warmup):
         restore()
-        sccl.sccl_execute(plan, work, stream)
+        execute(plan, work, stream)
     torch.cuda.synchronize()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     torch.cuda.synchronize()
@@ -78,7 +79,7 @@ def time_workload(wl, steps, warmup, options=None, keep=False):
     for a, b in evs:
         restore()                      # outside the timed window
         a.record(stream)
-        sccl.sccl_execute(plan, work, stream)
+        execute(plan, work, stream)
         b.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -227,25 +228,33 @@ def main():
         for coll in ("allgather", "allreduce"):
             for size in workloads.sweep_sizes():
                 names.append((f"cfg5 {coll} {size}", workloads.sweep_workload(coll, size)))
-        for label, w in names:
-            steps = 5 if w.bytes_per_rank >= (1 << 30) else 20
-            r = time_workload(w, steps, 3)
+        def median_us(w, steps, mode):
+            r = time_workload(w, steps, 3, mode=mode)
             m = sorted(r["ms"])
-            med = m[len(m) // 2]
-            s = r["stats"]
-            rows.append((label, s["num_nodes"], w.bytes_per_rank, s["chunk_bytes"], s["num_steps"], s["bytes_min"],
-                         med * 1e3, m[0] * 1e3, s["bytes_min"] / (med * 1e-3) / 1e9, s["block_threads"],
-                         s["vectors_per_thread"], s["grid_workgroups"]))
-            print(f"[report] {label}: {med * 1e3:.1f} us median, {rows[-1][8]:.1f} GB/s", file=sys.stderr, flush=True)
+            out = (m[len(m) // 2] * 1e3, m[0] * 1e3, r["stats"])
             del r
             torch.cuda.empty_cache()
+            return out
+
+        for label, w in names:
+            steps = 5 if w.bytes_per_rank >= (1 << 30) else 20
+            med, mn, s = median_us(w, steps, "sccl_execute")
+            step_med, _, _ = median_us(w, steps, "sccl_execute_stepwise")
+            cpy_med = median_us(w, steps, "sccl_execute_memcpy")[0] if s["num_reduce_groups"] == 0 else None
+            rows.append((label, s["num_nodes"], w.bytes_per_rank, s["chunk_bytes"], s["num_steps"], s["bytes_min"],
+                         med, mn, s["bytes_min"] / (med * 1e-6) / 1e9, s["block_threads"],
+                         s["vectors_per_thread"], s["grid_workgroups"], step_med, cpy_med))
+            print(f"[report] {label}: fused {med:.1f} us ({rows[-1][8]:.1f} GB/s), per-step kernels {step_med:.1f} us, "
+                  f"per-send copies {cpy_med if cpy_med is None else round(cpy_med, 1)} us", file=sys.stderr, flush=True)
         os.makedirs(os.path.dirname(os.path.abspath(args.report)), exist_ok=True)
         with open(args.report, "w") as f:
-            f.write("| workload | P | bytes/rank | chunk bytes | S | bytes_min | median us | min us | effective GB/s | % of 8 TB/s | block | vec/lane | grid |\n")
-            f.write("|---|---|---|---|---|---|---|---|---|---|---|---|---|\n")
+            f.write("| workload | P | bytes/rank | chunk bytes | S | bytes_min | fused: median us | min us | effective GB/s | % of 8 TB/s "
+                    "| block | vec/lane | grid | one kernel per step: us | one copy per send: us |\n")
+            f.write("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|\n")
             for r in rows:
                 f.write(f"| {r[0]} | {r[1]} | {r[2]} | {r[3]} | {r[4]} | {r[5]} | {r[6]:.1f} | {r[7]:.1f} | {r[8]:.1f} | "
-                        f"{100 * r[8] / HBM_PEAK_GBS:.1f} | {r[9]} | {r[10]} | {r[11]} |\n")
+                        f"{100 * r[8] / HBM_PEAK_GBS:.1f} | {r[9]} | {r[10]} | {r[11]} | {r[12]:.1f} | "
+                        f"{'-' if r[13] is None else format(r[13], '.1f')} |\n")
     print(json.dumps(line), flush=True)
 
 
