@@ -95,6 +95,14 @@ typedef struct {
     int32_t combining;
     sccl_dtype_t dtype;
     int64_t elems_per_chunk;       /* >= 0; chunk bytes = elems_per_chunk * sizeof(dtype) */
+    /* Optional layout.  The paper numbers chunks globally (section 3.2.2) but leaves open where a node
+     * keeps them.  slot == NULL: every rank keeps chunk c at chunk position c of a G-chunk buffer.
+     * Otherwise slot is G x P row-major, slot[c*P + n] = chunk position of chunk c in rank n's buffer
+     * of slots_per_rank chunks, or -1 if rank n never holds chunk c.  Required (else
+     * SCCL_ERR_INVALID_ARG): a position for every (c, n) in pre and for the source and destination of
+     * every send; positions in range; two chunks never share a position on one rank. */
+    const int32_t* slot;
+    int32_t slots_per_rank;
 } sccl_collective_t;
 
 /* One send (c, n, n', s) of section 3.3 plus, for combining collectives, what
@@ -134,7 +142,7 @@ typedef struct {
     int64_t num_reduce_groups;     /* (step, chunk, dst) groups */
     int32_t max_fan_in, max_fan_out;
     int64_t chunk_bytes;
-    int64_t bytes_per_rank;        /* G * chunk_bytes */
+    int64_t bytes_per_rank;        /* G (or slots_per_rank) * chunk_bytes */
     int64_t bytes_min;             /* sum over copy groups of (1 + k) chunks and over reduce groups of (k + 2) chunks */
     int64_t bytes_unfused;         /* 2 chunks per COPY send + 3 per REDUCE send */
     /* launch shape chosen for the kernel */
@@ -165,7 +173,7 @@ sccl_status_t sccl_plan_create_ex(const sccl_topology_t* topology, const sccl_co
 /*
  * Execute the plan in place: all S steps of sends (section 3.3; lowered as one
  * kernel as in section 4, "single kernel") on the P device buffers
- * rank_buffers[0..P-1], each G * elems_per_chunk elements, 16-byte aligned and
+ * rank_buffers[0..P-1], each G (or slots_per_rank) * elems_per_chunk elements, 16-byte aligned and
  * pairwise disjoint (checked: SCCL_ERR_ALIGNMENT / SCCL_ERR_OVERLAP).
  * `stream` is a hipStream_t (NULL = the default stream).  The call enqueues
  * one kernel and returns; it does not synchronise and does not allocate.  The

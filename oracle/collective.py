@@ -115,3 +115,25 @@ def reduce(P: int, C: int = 1, root: int = 0) -> Collective:
 def allreduce(P: int, G: int) -> Collective:
     """Reducescatter followed by Allgather (section 3.5); the tables count its chunks per node, so C = G."""
     return Collective("allreduce", P, G, rel_all(G, P), rel_all(G, P), True, G)
+
+
+def compact_slots(coll: Collective, sends: np.ndarray):
+    """A slot map that gives every rank room only for the chunks it ever holds.
+
+    The paper numbers chunks globally (section 3.2.2) and leaves the placement inside a node's
+    memory open.  Rank n gets one slot per chunk that is in pre at n or that some send delivers to
+    n, in ascending chunk order; all ranks' buffers are sized to the largest count.  Returns
+    (slot, slots_per_rank) with slot a G x P int32 array, -1 where rank n never holds chunk c.
+    """
+    G, P = coll.num_chunks, coll.num_nodes
+    held = coll.pre.astype(bool).copy()
+    for (c, n, m, s, op) in np.asarray(sends).reshape(-1, 5).tolist():
+        held[c, m] = True
+    slot = np.full((G, P), -1, dtype=np.int32)
+    for n in range(P):
+        k = 0
+        for c in range(G):
+            if held[c, n]:
+                slot[c, n] = k
+                k += 1
+    return slot, int(held.sum(axis=0).max())

@@ -8,7 +8,10 @@
  *
  *   every rank n owns one buffer of G chunks, chunk c at element offset
  *   c * elems_per_chunk in every buffer (global chunk numbering, section
- *   3.2.2);
+ *   3.2.2); optionally a slot map says instead that chunk c sits in slot
+ *   slot[c*P + n] of rank n's buffer (the paper numbers chunks globally but
+ *   does not prescribe where a node stores them: a node only needs room for
+ *   the chunks it ever holds);
  *
  *   for s = 0 .. S-1, for the sends of step s in array order
  *     COPY   (c, n -> n'):  buf[n'][c] = buf[n][c]
@@ -165,7 +168,9 @@ static void reduce_group(int dtype, void *dst, const void **srcs, int k, int64_t
 
 /*
  * sends: num_sends rows of 5 int32 (chunk, src, dst, step, op), array order
- * significant.  bufs: P host pointers, each G * elems_per_chunk elements.
+ * significant.  bufs: P host pointers, each G * elems_per_chunk elements, or
+ * slots_per_rank * elems_per_chunk when a slot map (G x P int32, -1 = rank
+ * never holds the chunk) is given; slot == NULL means slot c for every rank.
  * first_elem / num_elems: the element range WITHIN every chunk to process
  * (0, elems_per_chunk for the whole thing); elements are independent, so a
  * sub-range is the same computation on a sample.
@@ -173,7 +178,8 @@ static void reduce_group(int dtype, void *dst, const void **srcs, int k, int64_t
  */
 int32_t oracle_execute(int32_t P, int32_t G, int64_t elems_per_chunk, int32_t dtype, int32_t S,
                        int64_t num_sends, const int32_t *sends, void *const *bufs,
-                       int64_t first_elem, int64_t num_elems, int32_t nthreads)
+                       int64_t first_elem, int64_t num_elems, int32_t nthreads,
+                       const int32_t *slot, int32_t slots_per_rank)
 {
     if (P < 1 || G < 1 || elems_per_chunk < 0 || S < 0 || num_sends < 0) return -1;
     if (dtype != DT_I32 && dtype != DT_F32 && dtype != DT_F16) return -1;
@@ -189,26 +195,30 @@ int32_t oracle_execute(int32_t P, int32_t G, int64_t elems_per_chunk, int32_t dt
             t[3] < 0 || t[3] >= S || (t[4] != OP_COPY && t[4] != OP_REDUCE)) {
             free(done); free(srcs); return -1;
         }
+        if (slot) {
+            int32_t a = slot[(int64_t)t[0] * P + t[1]], b = slot[(int64_t)t[0] * P + t[2]];
+            if (a < 0 || a >= slots_per_rank || b < 0 || b >= slots_per_rank) { free(done); free(srcs); return -1; }
+        }
     }
     for (int32_t s = 0; s < S; s++) {
         for (int64_t i = 0; i < num_sends; i++) {
             const int32_t *t = sends + 5 * i;
             if (t[3] != s || done[i]) continue;
             int32_t c = t[0], n = t[1], m = t[2];
-            int64_t off = ((int64_t)c * elems_per_chunk + first_elem) * eb;
+#define CHUNK_AT(rank) (((int64_t)(slot ? slot[(int64_t)c * P + (rank)] : c) * elems_per_chunk + first_elem) * eb)
             if (t[4] == OP_COPY) {
-                copy_chunk((uint8_t *)bufs[m] + off, (const uint8_t *)bufs[n] + off, num_elems, eb, nthreads);
+                copy_chunk((uint8_t *)bufs[m] + CHUNK_AT(m), (const uint8_t *)bufs[n] + CHUNK_AT(n), num_elems, eb, nthreads);
                 done[i] = 1;
             } else {
                 int k = 0;
                 for (int64_t j = i; j < num_sends; j++) {
                     const int32_t *u = sends + 5 * j;
                     if (u[3] == s && u[4] == OP_REDUCE && u[0] == c && u[2] == m && !done[j]) {
-                        srcs[k++] = (const uint8_t *)bufs[u[1]] + off;
+                        srcs[k++] = (const uint8_t *)bufs[u[1]] + CHUNK_AT(u[1]);
                         done[j] = 1;
                     }
                 }
-                reduce_group(dtype, (uint8_t *)bufs[m] + off, srcs, k, num_elems, nthreads);
+                reduce_group(dtype, (uint8_t *)bufs[m] + CHUNK_AT(m), srcs, k, num_elems, nthreads);
             }
         }
     }

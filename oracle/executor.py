@@ -38,7 +38,7 @@ def _load():
         lib.oracle_execute.restype = ctypes.c_int32
         lib.oracle_execute.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
                                        ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
-                                       ctypes.c_int64, ctypes.c_int64, ctypes.c_int32]
+                                       ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32]
         lib.oracle_f16_to_f32.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
         lib.oracle_f32_to_f16.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
         lib.oracle_max_threads.restype = ctypes.c_int32
@@ -52,12 +52,21 @@ def max_threads() -> int:
 
 def execute(dtype: str, num_chunks: int, elems_per_chunk: int, sched: Schedule,
             bufs: Sequence[np.ndarray], threads: int = 1,
-            first_elem: int = 0, num_elems: Optional[int] = None) -> None:
-    """Run the schedule in place on P host buffers (one contiguous array of G*elems_per_chunk per rank)."""
+            first_elem: int = 0, num_elems: Optional[int] = None,
+            slot: Optional[np.ndarray] = None, slots_per_rank: Optional[int] = None) -> None:
+    """Run the schedule in place on P host buffers.
+
+    Default layout: one contiguous array of G*elems_per_chunk per rank, chunk c in slot c.  With `slot`
+    (G x P int32, -1 = never held) rank n keeps chunk c in slot[c, n] of a buffer of slots_per_rank chunks.
+    """
     code, npdt = DTYPES[dtype]
     P = len(bufs)
+    per_rank = num_chunks if slot is None else int(slots_per_rank)
+    slot_arr = None if slot is None else np.ascontiguousarray(slot, dtype=np.int32)
+    if slot_arr is not None and slot_arr.shape != (num_chunks, P):
+        raise ValueError("slot map must be G x P")
     for b in bufs:
-        if b.dtype != npdt or not b.flags["C_CONTIGUOUS"] or b.size != num_chunks * elems_per_chunk:
+        if b.dtype != npdt or not b.flags["C_CONTIGUOUS"] or b.size != per_rank * elems_per_chunk:
             raise ValueError("rank buffer has the wrong dtype, layout or size")
     if num_elems is None:
         num_elems = elems_per_chunk - first_elem
@@ -65,7 +74,8 @@ def execute(dtype: str, num_chunks: int, elems_per_chunk: int, sched: Schedule,
     ptrs = (ctypes.c_void_p * P)(*[b.ctypes.data for b in bufs])
     rc = _load().oracle_execute(P, num_chunks, elems_per_chunk, code, sched.num_steps, sends.shape[0],
                                 sends.ctypes.data, ctypes.cast(ptrs, ctypes.c_void_p),
-                                first_elem, num_elems, threads)
+                                first_elem, num_elems, threads,
+                                None if slot_arr is None else slot_arr.ctypes.data, per_rank)
     if rc != 0:
         raise ValueError("oracle_execute rejected its arguments")
 

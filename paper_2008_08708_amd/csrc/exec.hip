@@ -70,6 +70,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(char* base, uint32_t
     return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
 }
 
+struct Tile;
+// Descriptor of one operand (rank | slot << 8) on the current tile.
+template <class Args>
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t operand_rsrc(const Args& a, int32_t w, const Tile& t);
+
 template <int W> struct BufIO;
 template <> struct BufIO<16> {
     static __device__ __forceinline__ u32x4 ld(__amdgpu_buffer_rsrc_t r, uint32_t v, uint32_t s) {
@@ -162,11 +167,18 @@ template <int W> struct Acc<SCCL_F16, W> {           // binary16 in memory, bina
 
 // What every op of one work item shares.
 struct Tile {
-    int64_t item_off;        // byte offset of the tile in every rank buffer
+    int64_t chunk_bytes;
+    int64_t in_chunk;        // byte offset of the tile inside its chunk
     uint32_t bytes;          // bytes of the tile that exist (the last tile of a chunk may be short)
     uint32_t lane_off;       // this lane's byte offset in a row
     uint32_t ustride;        // bytes per row
 };
+
+template <class Args>
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t operand_rsrc(const Args& a, int32_t w, const Tile& t) {
+    char* base = a.bufs[w & OPERAND_RANK_MASK] + (int64_t)(w >> OPERAND_RANK_BITS) * t.chunk_bytes + t.in_chunk;
+    return tile_rsrc(base, t.bytes);
+}
 
 // NS sources of a reduce group (NS is a compile-time batch size): all scalar work (operand words,
 // pointers, descriptors) first, then every load back to back, then the adds in order.  In the
@@ -179,7 +191,7 @@ __device__ __forceinline__ void reduce_batch(Acc<DT, W> (&acc)[U], const typenam
     V x[NS][U];
     __amdgpu_buffer_rsrc_t r[NS];
 #pragma unroll
-    for (int j = 0; j < NS; j++) r[j] = tile_rsrc(a.bufs[srcs[j]] + t.item_off, t.bytes);
+    for (int j = 0; j < NS; j++) r[j] = operand_rsrc(a, srcs[j], t);
 #pragma unroll
     for (int j = 0; j < NS; j++) load_rows<W, U>(x[j], r[j], t.lane_off, t.ustride);
     if (FIRST) {
@@ -213,15 +225,15 @@ __device__ __forceinline__ int32_t do_op(const Args& a, table_ptr op, const Tile
         // copy group: one read, k writes
         const int32_t ws = op[1];
         V x[U];
-        load_rows<W, U>(x, tile_rsrc(a.bufs[ws] + t.item_off, t.bytes), t.lane_off, t.ustride);
+        load_rows<W, U>(x, operand_rsrc(a, ws, t), t.lane_off, t.ustride);
         for (int32_t d = 0; d < k; d++) {
             const int32_t wd = op[2 + d];
-            store_rows<W, U>(x, tile_rsrc(a.bufs[wd] + t.item_off, t.bytes), t.lane_off, t.ustride);
+            store_rows<W, U>(x, operand_rsrc(a, wd, t), t.lane_off, t.ustride);
         }
     } else {
         // reduce group: destination first, then the k sources in schedule order
         const int32_t wd = op[1];
-        const __amdgpu_buffer_rsrc_t rd = tile_rsrc(a.bufs[wd] + t.item_off, t.bytes);
+        const __amdgpu_buffer_rsrc_t rd = operand_rsrc(a, wd, t);
         Acc<DT, W> acc[U];
         V d0[U];
         load_rows<W, U>(d0, rd, t.lane_off, t.ustride);
@@ -250,13 +262,14 @@ __global__ void __launch_bounds__(256) sccl_exec_kernel(const ExecArgs a) {
     Tile t;
     t.lane_off = threadIdx.x * W;
     t.ustride = blockDim.x * W;
+    t.chunk_bytes = a.chunk_bytes;
     table_ptr offs = (table_ptr)a.chunk_off;
     for (int64_t item = blockIdx.x; item < a.num_items; item += gridDim.x) {
         const int32_t c = (int32_t)(item / a.tiles_per_chunk);
         const int32_t tile = (int32_t)(item - (int64_t)c * a.tiles_per_chunk);
         const int64_t in_chunk = (int64_t)tile * tile_bytes;
         const int64_t rest = a.chunk_bytes - in_chunk;
-        t.item_off = (int64_t)c * a.chunk_bytes + in_chunk;
+        t.in_chunk = in_chunk;
         t.bytes = rest < (int64_t)tile_bytes ? (uint32_t)rest : tile_bytes;
         table_ptr op = (table_ptr)a.prog + offs[c];
         table_ptr end = (table_ptr)a.prog + offs[c + 1];
@@ -268,7 +281,7 @@ __global__ void __launch_bounds__(256) sccl_exec_kernel(const ExecArgs a) {
 // executes the groups of ONE step; a work item is (group, tile).  The kernel boundary is the
 // global synchronisation between steps.  Kept as a comparator for the fused kernel above.
 struct StepArgs {
-    const int32_t* step_prog;     // per group: chunk | header | anchor | others...
+    const int32_t* step_prog;     // per group: header | anchor | others...
     const int32_t* group_off;     // word offset of every group, in step order
     int64_t chunk_bytes;
     int64_t num_items;            // groups of this step x tiles per chunk
@@ -283,17 +296,17 @@ __global__ void __launch_bounds__(256) sccl_step_kernel(const StepArgs a) {
     Tile t;
     t.lane_off = threadIdx.x * W;
     t.ustride = blockDim.x * W;
+    t.chunk_bytes = a.chunk_bytes;
     table_ptr goff = (table_ptr)a.group_off;
     for (int64_t item = blockIdx.x; item < a.num_items; item += gridDim.x) {
         const int32_t g = (int32_t)(item / a.tiles_per_chunk);
         const int32_t tile = (int32_t)(item - (int64_t)g * a.tiles_per_chunk);
         table_ptr op = (table_ptr)a.step_prog + goff[a.first_group + g];
-        const int32_t c = op[0];
         const int64_t in_chunk = (int64_t)tile * tile_bytes;
         const int64_t rest = a.chunk_bytes - in_chunk;
-        t.item_off = (int64_t)c * a.chunk_bytes + in_chunk;
+        t.in_chunk = in_chunk;
         t.bytes = rest < (int64_t)tile_bytes ? (uint32_t)rest : tile_bytes;
-        do_op<DT, W, U>(a, op + 1, t);
+        do_op<DT, W, U>(a, op, t);
     }
 }
 
@@ -482,8 +495,8 @@ sccl_status_t sccl_execute_memcpy(const sccl_plan_t* plan, void* const* rank_buf
     const size_t cs = (size_t)plan->stats.chunk_bytes;
     if (cs == 0) return SCCL_OK;
     for (const auto& t : plan->copy_sends) {
-        char* dst = (char*)rank_buffers[t.dst] + (size_t)t.chunk * cs;
-        const char* src = (const char*)rank_buffers[t.src] + (size_t)t.chunk * cs;
+        char* dst = (char*)rank_buffers[t.dst] + (size_t)t.dst_slot * cs;
+        const char* src = (const char*)rank_buffers[t.src] + (size_t)t.src_slot * cs;
         if (hipMemcpyAsync(dst, src, cs, hipMemcpyDeviceToDevice, (hipStream_t)stream) != hipSuccess) return SCCL_ERR_DEVICE;
     }
     return SCCL_OK;

@@ -81,6 +81,30 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
         if (t.op != SCCL_COPY && t.op != SCCL_REDUCE_SUM) return SCCL_ERR_INVALID_ARG;
         if (t.op == SCCL_REDUCE_SUM && !coll->combining) return SCCL_ERR_INVALID_ARG;
     }
+    // ---- layout: where rank n keeps chunk c
+    const int32_t slots = coll->slot ? coll->slots_per_rank : G;
+    if (slots < 1 || slots > MAX_SLOTS) return SCCL_ERR_INVALID_ARG;
+    auto slot_of = [&](int32_t c, int32_t n) -> int32_t { return coll->slot ? coll->slot[(size_t)c * P + n] : c; };
+    if (coll->slot) {
+        std::vector<uint8_t> taken((size_t)P * slots, 0);
+        for (int32_t c = 0; c < G; c++)
+            for (int32_t n = 0; n < P; n++) {
+                const int32_t sl = coll->slot[(size_t)c * P + n];
+                if (sl < -1 || sl >= slots) return SCCL_ERR_INVALID_ARG;
+                if (sl < 0) {
+                    if (coll->pre[(size_t)c * P + n]) return SCCL_ERR_INVALID_ARG;
+                    continue;
+                }
+                if (taken[(size_t)n * slots + sl]) return SCCL_ERR_INVALID_ARG;
+                taken[(size_t)n * slots + sl] = 1;
+            }
+        for (int64_t i = 0; i < N; i++) {
+            const sccl_send_t& t = sched->sends[i];
+            if (slot_of(t.chunk, t.src) < 0 || slot_of(t.chunk, t.dst) < 0) return SCCL_ERR_INVALID_ARG;
+        }
+    }
+    auto operand = [&](int32_t c, int32_t n) -> int32_t { return n | (slot_of(c, n) << OPERAND_RANK_BITS); };
+
     for (int64_t i = 0; i < N; i++) {
         const sccl_send_t& t = sched->sends[i];
         const size_t e = (size_t)t.src * P + t.dst;
@@ -196,15 +220,14 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
         plan->step_first[(size_t)s] = (int32_t)plan->group_off.size();
         for (int64_t q = lo; q < hi; q++) {
             const sccl_send_t& t = sched->sends[order[(size_t)q]];
-            if (t.op == SCCL_COPY) plan->copy_sends.push_back({t.chunk, t.src, t.dst});
+            if (t.op == SCCL_COPY) plan->copy_sends.push_back({t.src, slot_of(t.chunk, t.src), t.dst, slot_of(t.chunk, t.dst)});
         }
         for (Group& g : groups) {
             const int32_t k = (int32_t)g.others.size();
             plan->group_off.push_back((int32_t)plan->step_prog.size());
-            plan->step_prog.push_back(g.chunk);
             plan->step_prog.push_back(g.kind | (k << 8));
-            plan->step_prog.push_back(g.anchor);
-            for (int32_t o : g.others) plan->step_prog.push_back(o);
+            plan->step_prog.push_back(operand(g.chunk, g.anchor));
+            for (int32_t o : g.others) plan->step_prog.push_back(operand(g.chunk, o));
             if (g.kind == 0) { n_copy_groups++; chunks_min += 1 + k; max_out = std::max(max_out, k); }
             else             { n_reduce_groups++; chunks_min += k + 2; max_in = std::max(max_in, k); }
             per_chunk[(size_t)g.chunk].push_back(std::move(g));
@@ -222,8 +245,8 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
         plan->chunk_off[(size_t)c] = (int32_t)plan->prog.size();
         for (const Group& g : per_chunk[(size_t)c]) {
             plan->prog.push_back(g.kind | ((int32_t)g.others.size() << 8));
-            plan->prog.push_back(g.anchor);
-            for (int32_t o : g.others) plan->prog.push_back(o);
+            plan->prog.push_back(operand(c, g.anchor));
+            for (int32_t o : g.others) plan->prog.push_back(operand(c, o));
         }
     }
     plan->chunk_off[(size_t)G] = (int32_t)plan->prog.size();
@@ -243,7 +266,7 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
     st.num_copy_groups = n_copy_groups; st.num_reduce_groups = n_reduce_groups;
     st.max_fan_in = max_in; st.max_fan_out = max_out;
     st.chunk_bytes = chunk_bytes;
-    st.bytes_per_rank = chunk_bytes * G;
+    st.bytes_per_rank = chunk_bytes * slots;
     st.bytes_min = chunks_min * chunk_bytes;
     st.bytes_unfused = chunks_unfused * chunk_bytes;
 

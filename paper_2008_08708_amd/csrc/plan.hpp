@@ -11,9 +11,14 @@
 // same offset in every rank buffer), so the only ordering the schedule imposes
 // is between the ops of ONE chunk.  An op is
 //   word 0      : kind (bit 0: 0 copy group, 1 reduce group) | count << 8
-//   word 1      : copy: the source rank          reduce: the destination rank
-//   word 2..    : copy: `count` destination ranks reduce: `count` source ranks, in schedule order
+//   word 1      : copy: the source operand       reduce: the destination operand
+//   word 2..    : copy: `count` destination operands; reduce: `count` source operands, in schedule order
+// An operand is  rank | slot << 8 : the rank whose buffer is touched and the chunk position of this
+// chunk in that buffer (the chunk id itself under the default layout).
 constexpr int32_t OP_KIND_REDUCE = 1;
+constexpr int32_t OPERAND_RANK_BITS = 8;
+constexpr int32_t OPERAND_RANK_MASK = (1 << OPERAND_RANK_BITS) - 1;
+constexpr int32_t MAX_SLOTS = 1 << (31 - OPERAND_RANK_BITS);
 
 struct sccl_plan {
     // problem
@@ -25,13 +30,12 @@ struct sccl_plan {
     // compiled program (host copy)
     std::vector<int32_t> prog;
     std::vector<int32_t> chunk_off;     // G + 1 offsets into prog
-    // the same groups in step order, for the step-per-launch lowering: per group
-    //   chunk | header | anchor | others...
+    // the same groups in step order, for the step-per-launch lowering
     std::vector<int32_t> step_prog;
     std::vector<int32_t> group_off;     // word offset of every group in step_prog, in step order
     std::vector<int32_t> step_first;    // S + 1 indices into group_off
     // COPY sends in step order (array order inside a step), for the copy-engine lowering
-    struct CopySend { int32_t chunk, src, dst; };
+    struct CopySend { int32_t src, src_slot, dst, dst_slot; };
     std::vector<CopySend> copy_sends;
     sccl_stats_t stats{};
     sccl_options_t opts{};

@@ -41,7 +41,8 @@ class sccl_topology_t(ctypes.Structure):
 
 class sccl_collective_t(ctypes.Structure):
     _fields_ = [("num_global_chunks", ctypes.c_int32), ("pre", ctypes.c_void_p), ("post", ctypes.c_void_p),
-                ("combining", ctypes.c_int32), ("dtype", ctypes.c_int32), ("elems_per_chunk", ctypes.c_int64)]
+                ("combining", ctypes.c_int32), ("dtype", ctypes.c_int32), ("elems_per_chunk", ctypes.c_int64),
+                ("slot", ctypes.c_void_p), ("slots_per_rank", ctypes.c_int32)]
 
 
 class sccl_send_t(ctypes.Structure):
@@ -141,6 +142,8 @@ class Collective:
     combining: bool
     dtype: str                                            # "i32" | "f32" | "f16"
     elems_per_chunk: int
+    slot: Optional[np.ndarray] = None                     # optional G x P int32 layout, -1 = never held
+    slots_per_rank: int = 0
 
 
 @dataclass
@@ -187,9 +190,11 @@ def sccl_plan_create(topology: Topology, collective: Collective, schedule: Sched
     topo = sccl_topology_t(int(topology.num_nodes), ctypes.cast(bws, ctypes.POINTER(sccl_bw_t)), len(topology.bw))
     pre = np.ascontiguousarray(collective.pre, dtype=np.uint8)
     post = np.ascontiguousarray(collective.post, dtype=np.uint8)
+    slot = None if collective.slot is None else np.ascontiguousarray(collective.slot, dtype=np.int32)
     coll = sccl_collective_t(int(collective.num_global_chunks), pre.ctypes.data, post.ctypes.data,
                              int(bool(collective.combining)), DTYPE_CODES[collective.dtype],
-                             int(collective.elems_per_chunk))
+                             int(collective.elems_per_chunk),
+                             None if slot is None else slot.ctypes.data, int(collective.slots_per_rank))
     rounds = np.ascontiguousarray(schedule.rounds, dtype=np.int32)
     sends = np.ascontiguousarray(schedule.sends, dtype=np.int32).reshape(-1, 5)
     sched = sccl_schedule_t(len(rounds), rounds.ctypes.data, sends.ctypes.data, sends.shape[0])

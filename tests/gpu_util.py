@@ -22,14 +22,14 @@ def host_inputs(dist, dtype, seed, P, G, epc, pre=None):
     return bufs
 
 
-def run_both(topo, coll, sched, dtype, bufs, epc, options=None, label="", mode="sccl_execute"):
+def run_both(topo, coll, sched, dtype, bufs, epc, options=None, label="", mode="sccl_execute", slot=None, slots_per_rank=0):
     """Oracle on copies of `bufs`, library on device copies; returns (oracle buffers, gpu buffers as numpy)."""
     import torch
     print(f"[case] {label} {mode} P={coll.num_nodes} G={coll.num_chunks} epc={epc} dtype={dtype} opts={options}", flush=True)
     want = [b.copy() for b in bufs]
-    ex.execute(dtype, coll.num_chunks, epc, sched, want)
+    ex.execute(dtype, coll.num_chunks, epc, sched, want, slot=slot, slots_per_rank=slots_per_rank)
     dev = [torch.from_numpy(b.copy()).cuda() for b in bufs]
-    plan = sccl.sccl_plan_create(*to_binding(topo, coll, sched, dtype, epc), options=options)
+    plan = sccl.sccl_plan_create(*to_binding(topo, coll, sched, dtype, epc, slot, slots_per_rank), options=options)
     getattr(sccl, mode)(plan, dev)
     torch.cuda.synchronize()
     got = [d.cpu().numpy() for d in dev]

@@ -61,3 +61,54 @@ def test_reduce_to_a_root(topo, dtype, dist):
         for b in bufs:
             direct = direct + b.view(np.uint32)
         assert (got[root].view(np.uint32) == direct).all()
+
+
+@pytest.mark.parametrize("topo", TOPOS, ids=[t.name for t in TOPOS])
+def test_alltoall_in_a_compact_layout(topo):
+    P = topo.num_nodes
+    coll = col.alltoall(P, P)
+    s = gen.greedy_route(topo, coll)
+    slot, per_rank = col.compact_slots(coll, s.sends)
+    epc = 1024 + 4 * 9
+    rng_bufs = [inputs.generate("uniform", "f32", 47, n, 0, per_rank * epc) for n in range(P)]
+    for n in range(P):                                    # positions of chunks the rank does not hold at the start are undefined
+        owned = {int(slot[c, n]) for c in range(coll.num_chunks) if coll.pre[c, n]}
+        for k in range(per_rank):
+            if k not in owned:
+                inputs.poison(rng_bufs[n], k * epc, (k + 1) * epc)
+    want, got = run_both(topo, coll, s, "f32", rng_bufs, epc, label=f"alltoall-compact-{topo.name}", slot=slot, slots_per_rank=per_rank)
+    assert_same_bits(want, got)
+    for j in range(P):                                    # rank j's block n came from rank n
+        for n in range(P):
+            c = j * P + n
+            a = got[j][slot[c, j] * epc:(slot[c, j] + 1) * epc]
+            b = rng_bufs[n][slot[c, n] * epc:(slot[c, n] + 1) * epc]
+            assert (bits(a) == bits(b)).all()
+
+
+@pytest.mark.parametrize("mode", ["sccl_execute", "sccl_execute_stepwise"])
+def test_allreduce_with_permuted_positions(mode):
+    # every rank keeps the chunks in its own random order: nothing may assume position == chunk id
+    topo = tp.hcm8()
+    ag = col.allgather(8, 2)
+    sched, coll = gen.compose_allreduce(gen.greedy_bfs(topo, ag), ag)
+    G, P, epc = coll.num_chunks, 8, 2048 + 12
+    rng = np.random.default_rng(5)
+    slot = np.stack([rng.permutation(G + 3)[:G] for _ in range(P)], axis=1).astype(np.int32)
+    bufs = [inputs.generate("normal", "f16", 49, n, 0, (G + 3) * epc) for n in range(P)]
+    want, got = run_both(topo, coll, sched, "f16", bufs, epc, label="allreduce-permuted", mode=mode, slot=slot, slots_per_rank=G + 3)
+    assert_same_bits(want, got)
+    ref = got[0][slot[0, 0] * epc:(slot[0, 0] + 1) * epc]
+    for n in range(1, P):
+        assert (bits(got[n][slot[0, n] * epc:(slot[0, n] + 1) * epc]) == bits(ref)).all()
+
+
+def test_memcpy_lowering_with_a_compact_layout():
+    topo = tp.ring(8)
+    coll = col.alltoall(8, 8)
+    s = gen.greedy_route(topo, coll)
+    slot, per_rank = col.compact_slots(coll, s.sends)
+    epc = 512 + 4
+    bufs = [inputs.generate("u32", "i32", 55, n, 0, per_rank * epc) for n in range(8)]
+    want, got = run_both(topo, coll, s, "i32", bufs, epc, label="alltoall-compact-memcpy", mode="sccl_execute_memcpy", slot=slot, slots_per_rank=per_rank)
+    assert_same_bits(want, got)

@@ -37,7 +37,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(sccl.sccl_edge_t) == 8
     assert ctypes.sizeof(sccl.sccl_bw_t) == 16
     assert ctypes.sizeof(sccl.sccl_topology_t) == 24
-    assert ctypes.sizeof(sccl.sccl_collective_t) == 40
+    assert ctypes.sizeof(sccl.sccl_collective_t) == 56
     assert ctypes.sizeof(sccl.sccl_send_t) == 20
     assert ctypes.sizeof(sccl.sccl_schedule_t) == 32
     assert ctypes.sizeof(sccl.sccl_options_t) == 20
@@ -217,3 +217,28 @@ def test_other_collectives_are_accepted():
         red = gen.invert(gen.greedy_route(topo, bc), bc)
         name, st = plan_status(topo.reversed(), col.reduce(P, 2, 0), red, "f16", 64)
         assert name == "SCCL_OK" and st["num_copy_groups"] == 0
+
+
+def test_slot_maps_are_validated():
+    topo, coll = tp.ring(4), col.alltoall(4, 4)
+    s = gen.greedy_route(topo, coll)
+    slot, per_rank = col.compact_slots(coll, s.sends)
+    assert per_rank < coll.num_chunks                       # the point of a compact layout
+    name, st = plan_status(topo, coll, s, "f32", 8, slot=slot, slots_per_rank=per_rank)
+    assert name == "SCCL_OK" and st["bytes_per_rank"] == per_rank * 32
+    # a chunk in pre without a position
+    bad = slot.copy(); bad[0, 0] = -1
+    assert plan_status(topo, coll, s, "f32", 8, slot=bad, slots_per_rank=per_rank)[0] == "SCCL_ERR_INVALID_ARG"
+    # a destination of a send without a position
+    c, n, m = s.sends[0, 0], s.sends[0, 1], s.sends[0, 2]
+    bad = slot.copy(); bad[c, m] = -1
+    assert plan_status(topo, coll, s, "f32", 8, slot=bad, slots_per_rank=per_rank)[0] == "SCCL_ERR_INVALID_ARG"
+    # two chunks in one position of one rank
+    bad = slot.copy()
+    held = np.nonzero(bad[:, 0] >= 0)[0]
+    bad[held[1], 0] = bad[held[0], 0]
+    assert plan_status(topo, coll, s, "f32", 8, slot=bad, slots_per_rank=per_rank)[0] == "SCCL_ERR_INVALID_ARG"
+    # out of range position, empty buffer
+    bad = slot.copy(); bad[held[0], 0] = per_rank
+    assert plan_status(topo, coll, s, "f32", 8, slot=bad, slots_per_rank=per_rank)[0] == "SCCL_ERR_INVALID_ARG"
+    assert plan_status(topo, coll, s, "f32", 8, slot=slot, slots_per_rank=0)[0] == "SCCL_ERR_INVALID_ARG"

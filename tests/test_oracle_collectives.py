@@ -136,3 +136,41 @@ def test_greedy_route_agrees_with_greedy_bfs_on_allgather_validity():
         assert validate(topo, ag, s).ok
         ar, arc = gen.compose_allreduce(s, ag)             # trees, so it can be inverted
         assert validate(topo, arc, ar).ok
+
+
+def test_compact_layout_gives_the_same_chunks_in_other_places():
+    for topo, coll in ((tp.ring(4), col.alltoall(4, 4)), (tp.hcm8(), col.alltoall(8, 8)), (tp.torus2d(4, 4), col.gather(16, 2, 3))):
+        P, G, epc = coll.num_nodes, coll.num_chunks, 6
+        s = gen.greedy_route(topo, coll)
+        slot, per_rank = col.compact_slots(coll, s.sends)
+        # every rank has room exactly for what it holds at some time; positions are distinct per rank
+        for n in range(P):
+            used = slot[:, n][slot[:, n] >= 0]
+            assert len(set(used.tolist())) == used.size and used.size <= per_rank
+        assert per_rank <= G
+        if coll.name == "alltoall":
+            assert per_rank < G                               # own chunks, received chunks, a few relayed ones
+        full = poisoned_inputs(coll, "f32", "uniform", 19, epc)
+        compact = []
+        for n in range(P):
+            b = np.empty(per_rank * epc, dtype=np.float32)
+            inputs.poison(b, 0, b.size)
+            for c in range(G):
+                if coll.pre[c, n]:
+                    b[slot[c, n] * epc:(slot[c, n] + 1) * epc] = full[n][c * epc:(c + 1) * epc]
+            compact.append(b)
+        ex.execute("f32", G, epc, s, full)
+        ex.execute("f32", G, epc, s, compact, slot=slot, slots_per_rank=per_rank)
+        for c in range(G):
+            for n in range(P):
+                if coll.post[c, n]:
+                    a = chunk(full[n], c, epc)
+                    b = chunk(compact[n], int(slot[c, n]), epc)
+                    assert (a == b).all()
+    # a send whose destination has no position is refused
+    topo, coll = tp.ring(4), col.alltoall(4, 4)
+    s = gen.greedy_route(topo, coll)
+    slot, per_rank = col.compact_slots(coll, s.sends)
+    slot[s.sends[0, 0], s.sends[0, 2]] = -1
+    with pytest.raises(ValueError):
+        ex.execute("f32", 16, 2, s, [np.zeros(per_rank * 2, np.float32) for _ in range(4)], slot=slot, slots_per_rank=per_rank)
