@@ -221,3 +221,19 @@ def test_copy_kernel():
         sccl.sccl_copy_kernel(dst, src, n * 4)
         torch.cuda.synchronize()
         assert torch.equal(src, dst)
+
+
+def test_synthesized_schedules_with_several_rounds_per_step():
+    # k > 0 schedules from the exact search: (2,2,3) on the DGX-1 graph -> Allreduce (16,4,6); (2,4,7) on the 8-ring
+    from oracle import synthesize as syn
+    for topo, (C, S, R), dtype, dist in ((tp.dgx1(), (2, 2, 3), "f32", "uniform"), (tp.ring(8), (2, 4, 7), "f16", "normal")):
+        ag = col.allgather(8, C)
+        base = syn.solve_instance(topo, ag, S, R)
+        sched, coll = gen.compose_allreduce(base, ag)
+        assert validate(topo, coll, sched).ok and max(sched.rounds) > 1
+        epc = 2048 + 8 * 7
+        bufs = host_inputs(dist, dtype, 61, 8, coll.num_chunks, epc)
+        want, got = run_both(topo, coll, sched, dtype, bufs, epc, label=f"synth-{topo.name}-{C}-{S}-{R}")
+        assert_same_bits(want, got)
+        for g in got[1:]:
+            assert (bits(g) == bits(got[0])).all()
