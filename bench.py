@@ -179,7 +179,11 @@ def main():
     torch.cuda.set_device(0)
     options = {k: v for k, v in (("block_threads", args.block_threads), ("vectors_per_thread", args.vectors_per_thread),
                                  ("max_workgroups", args.max_workgroups)) if v}
-    wl = workloads.WORKLOADS[args.workload]
+    if args.workload.startswith("cfg5:"):             # cfg5:<allgather|allreduce>:<bytes per rank>
+        _, coll_name, size = args.workload.split(":")
+        wl = workloads.sweep_workload(coll_name, int(size))
+    else:
+        wl = workloads.WORKLOADS[args.workload]
     run = time_workload(wl, args.steps, args.warmup, options or None, keep=True)
     st = run["stats"]
     ms = run["ms"]

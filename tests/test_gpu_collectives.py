@@ -112,3 +112,17 @@ def test_memcpy_lowering_with_a_compact_layout():
     bufs = [inputs.generate("u32", "i32", 55, n, 0, per_rank * epc) for n in range(8)]
     want, got = run_both(topo, coll, s, "i32", bufs, epc, label="alltoall-compact-memcpy", mode="sccl_execute_memcpy", slot=slot, slots_per_rank=per_rank)
     assert_same_bits(want, got)
+
+
+@pytest.mark.parametrize("epc", [2, 64, 1000])
+def test_small_chunks_of_other_collectives(epc):
+    topo = tp.hcm8()
+    for coll in (col.broadcast(8, 3, 1), col.alltoall(8, 8), col.gather(8, 2, 7)):
+        s = gen.greedy_route(topo, coll)
+        bufs = poisoned(coll, "f16", "normal", 73, epc)
+        want, got = run_both(topo, coll, s, "f16", bufs, epc, label=f"small-{coll.name}-{epc}")
+        assert_same_bits(want, got)
+        slot, per_rank = col.compact_slots(coll, s.sends)
+        cb = [inputs.generate("normal", "f16", 75, n, 0, per_rank * epc) for n in range(8)]
+        want, got = run_both(topo, coll, s, "f16", cb, epc, label=f"small-compact-{coll.name}-{epc}", slot=slot, slots_per_rank=per_rank)
+        assert_same_bits(want, got)
