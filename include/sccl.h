@@ -123,8 +123,6 @@ typedef struct {
 
 /* Options of sccl_plan_create_ex; zero-initialise for the defaults. */
 #define SCCL_PLAN_HOST_ONLY 1u     /* validate and compile only: touches no device; the plan cannot be executed */
-#define SCCL_PLAN_NO_BATCHING 2u   /* small chunks: walk the groups one by one instead of in batches of independent
-                                      groups (for comparison; results are identical) */
 typedef struct {
     uint32_t flags;
     int32_t block_threads;         /* 0 = choose from the chunk size; else 64, 128 or 256 */
@@ -152,8 +150,6 @@ typedef struct {
     int32_t block_threads, vectors_per_thread;
     int64_t num_work_items;        /* G * tiles per chunk */
     int32_t grid_workgroups;       /* 0 for a host-only plan */
-    int32_t num_batches;           /* > 0: small-chunk path, the groups of a chunk are issued in this many batches of
-                                      mutually independent groups (summed over chunks); 0: one group at a time */
 } sccl_stats_t;
 
 typedef struct sccl_plan sccl_plan_t;

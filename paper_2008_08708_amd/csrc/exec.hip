@@ -277,51 +277,6 @@ __global__ void __launch_bounds__(256) sccl_exec_kernel(const ExecArgs a) {
     }
 }
 
-// Small chunks: one workgroup row covers a whole chunk and the chunk's groups arrive as batches of
-// mutually independent groups (see plan.hpp).  All loads of a batch are issued back to back, then
-// the sums are formed and stored in slot order: one memory round trip per dependency level
-// instead of one per group.  Copies store the loaded bits untouched.
-template <int DT, int W>
-__global__ void __launch_bounds__(256) sccl_exec_batched_kernel(const ExecArgs a) {
-    typedef typename VecOf<W>::type V;
-    Tile t;
-    t.lane_off = threadIdx.x * W;
-    t.ustride = 0;
-    t.chunk_bytes = a.chunk_bytes;
-    t.in_chunk = 0;
-    t.bytes = (uint32_t)a.chunk_bytes;
-    table_ptr offs = (table_ptr)a.chunk_off;
-    for (int64_t item = blockIdx.x; item < a.num_items; item += gridDim.x) {
-        table_ptr p = (table_ptr)a.prog + offs[item];
-        table_ptr end = (table_ptr)a.prog + offs[item + 1];
-        while (p < end) {
-            const int32_t n = p[0];
-            V vals[BATCH_MAX_LOADS];
-#pragma unroll
-            for (int j = 0; j < BATCH_MAX_LOADS; j++)
-                if (j < n) vals[j] = BufIO<W>::ld(operand_rsrc(a, p[1 + j], t), t.lane_off, 0);
-            table_ptr q = p + 1 + n;
-            Acc<DT, W> acc;
-#pragma unroll
-            for (int j = 0; j < BATCH_MAX_LOADS; j++) {
-                if (j < n) {
-                    const int32_t ctl = q[0];
-                    const int32_t ns = ctl >> 8;
-                    V out = vals[j];
-                    if (!(ctl & SLOT_RAW)) {
-                        if (ctl & SLOT_START) acc.init(vals[j]);
-                        else acc.add(vals[j]);
-                        if (ns) out = acc.template done<V>();
-                    }
-                    for (int32_t s = 0; s < ns; s++) BufIO<W>::st(out, operand_rsrc(a, q[1 + s], t), t.lane_off, 0);
-                    q += 1 + ns;
-                }
-            }
-            p = q;
-        }
-    }
-}
-
 // The step-per-launch lowering (paper section 4, "multiple kernels, one per step"): one launch
 // executes the groups of ONE step; a work item is (group, tile).  The kernel boundary is the
 // global synchronisation between steps.  Kept as a comparator for the fused kernel above.
@@ -418,25 +373,6 @@ kernel_fn pick_w(int W, int U) {
         case 16: return pick_u<DT, 16>(U);
         case 8:  return pick_u<DT, 8>(U);
         default: return pick_u<DT, 4>(U);
-    }
-}
-
-template <int DT>
-kernel_fn pick_batched_w(int W) {
-    switch (W) {
-        case 16: return sccl_exec_batched_kernel<DT, 16>;
-        case 8:  return sccl_exec_batched_kernel<DT, 8>;
-        default: return sccl_exec_batched_kernel<DT, 4>;
-    }
-}
-
-kernel_fn pick_batched_kernel(sccl_dtype_t dt, int W) {
-    switch (dt) {
-        case SCCL_I32: return pick_batched_w<SCCL_I32>(W);
-        case SCCL_F32: return pick_batched_w<SCCL_F32>(W);
-        default:
-            if (W == 2) return sccl_exec_batched_kernel<SCCL_F16, 2>;
-            return pick_batched_w<SCCL_F16>(W);
     }
 }
 
@@ -579,8 +515,7 @@ sccl_status_t sccl_execute(const sccl_plan_t* plan, void* const* rank_buffers, v
     args.num_items = plan->num_items;
     args.tiles_per_chunk = plan->tiles_per_chunk;
     for (int32_t n = 0; n < P; n++) args.bufs[n] = (char*)rank_buffers[n];
-    kernel_fn fn = plan->batched ? pick_batched_kernel(plan->dtype, plan->vector_bytes)
-                                 : pick_kernel(plan->dtype, plan->vector_bytes, plan->vectors_per_thread);
+    kernel_fn fn = pick_kernel(plan->dtype, plan->vector_bytes, plan->vectors_per_thread);
     hipLaunchKernelGGL(fn, dim3((unsigned)plan->grid), dim3((unsigned)plan->block_threads), 0, (hipStream_t)stream, args);
     return hipGetLastError() == hipSuccess ? SCCL_OK : SCCL_ERR_DEVICE;
 }

@@ -238,6 +238,19 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
         for (int32_t n = 0; n < P; n++)
             if (coll->post[(size_t)c * P + n] && held[(size_t)c * P + n] != everyone) return SCCL_ERR_POSTCONDITION;
 
+    // ---- emit the program: per chunk, its groups in step order
+    plan->prog.clear();
+    plan->chunk_off.assign((size_t)G + 1, 0);
+    for (int32_t c = 0; c < G; c++) {
+        plan->chunk_off[(size_t)c] = (int32_t)plan->prog.size();
+        for (const Group& g : per_chunk[(size_t)c]) {
+            plan->prog.push_back(g.kind | ((int32_t)g.others.size() << 8));
+            plan->prog.push_back(operand(c, g.anchor));
+            for (int32_t o : g.others) plan->prog.push_back(operand(c, o));
+        }
+    }
+    plan->chunk_off[(size_t)G] = (int32_t)plan->prog.size();
+
     // ---- record the problem and the statistics
     plan->P = P; plan->G = G; plan->S = S;
     plan->dtype = coll->dtype;
@@ -294,98 +307,5 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
     st.vectors_per_thread = vt;
     st.num_work_items = plan->num_items;
     st.grid_workgroups = 0;
-
-    // ---- emit the program
-    plan->prog.clear();
-    plan->chunk_off.assign((size_t)G + 1, 0);
-    const bool shape_given = opts && (opts->block_threads || opts->vectors_per_thread);
-    plan->batched = !(opts && (opts->flags & SCCL_PLAN_NO_BATCHING)) && !shape_given &&
-                    plan->vecs_per_chunk > 0 && plan->vecs_per_chunk <= 256 && max_in + 1 <= BATCH_MAX_LOADS;
-    int32_t num_batches = 0;
-    if (!plan->batched) {
-        // per chunk, its groups in step order
-        for (int32_t c = 0; c < G; c++) {
-            plan->chunk_off[(size_t)c] = (int32_t)plan->prog.size();
-            for (const Group& g : per_chunk[(size_t)c]) {
-                plan->prog.push_back(g.kind | ((int32_t)g.others.size() << 8));
-                plan->prog.push_back(operand(c, g.anchor));
-                for (int32_t o : g.others) plan->prog.push_back(operand(c, o));
-            }
-        }
-    } else {
-        // One workgroup row covers the whole chunk.  Sort the chunk's groups by dependency level:
-        // a group that reads (c, n) comes at least one level after the last group that wrote it; a
-        // group that writes (c, n) comes no earlier than the last level that read it (inside a batch
-        // every load is issued before any store) and one level after the last write.  Groups of one
-        // level are independent and are issued together.
-        bt = (int32_t)(((plan->vecs_per_chunk + 63) / 64) * 64);
-        vt = 1;
-        plan->block_threads = bt; plan->vectors_per_thread = vt;
-        plan->tiles_per_chunk = 1; plan->num_items = G;
-        st.block_threads = bt; st.vectors_per_thread = vt; st.num_work_items = G;
-        std::vector<int32_t> last_write((size_t)P), last_read((size_t)P);
-        for (int32_t c = 0; c < G; c++) {
-            plan->chunk_off[(size_t)c] = (int32_t)plan->prog.size();
-            const std::vector<Group>& ops = per_chunk[(size_t)c];
-            std::fill(last_write.begin(), last_write.end(), -1);
-            std::fill(last_read.begin(), last_read.end(), -1);
-            std::vector<std::pair<int32_t, size_t>> order_by_level;
-            for (size_t i = 0; i < ops.size(); i++) {
-                const Group& g = ops[i];
-                int32_t L = 0;
-                auto reads = [&](int32_t n) { L = std::max(L, last_write[(size_t)n] + 1); };
-                auto writes = [&](int32_t n) { L = std::max(L, std::max(last_read[(size_t)n], last_write[(size_t)n] + 1)); };
-                reads(g.anchor);                                   // copy: the source; reduce: the destination's own value
-                if (g.kind == OP_KIND_REDUCE) { for (int32_t o : g.others) reads(o); writes(g.anchor); }
-                else { for (int32_t o : g.others) writes(o); }
-                last_read[(size_t)g.anchor] = std::max(last_read[(size_t)g.anchor], L);
-                if (g.kind == OP_KIND_REDUCE) {
-                    for (int32_t o : g.others) last_read[(size_t)o] = std::max(last_read[(size_t)o], L);
-                    last_write[(size_t)g.anchor] = L;
-                } else {
-                    for (int32_t o : g.others) last_write[(size_t)o] = L;
-                }
-                order_by_level.emplace_back(L, i);
-            }
-            std::stable_sort(order_by_level.begin(), order_by_level.end(),
-                             [](const std::pair<int32_t, size_t>& x, const std::pair<int32_t, size_t>& y) { return x.first < y.first; });
-            size_t q = 0;
-            while (q < order_by_level.size()) {
-                // cut a batch: same level, at most BATCH_MAX_LOADS loads
-                size_t e = q;
-                int32_t loads = 0;
-                while (e < order_by_level.size() && order_by_level[e].first == order_by_level[q].first) {
-                    const Group& g = ops[order_by_level[e].second];
-                    const int32_t need = g.kind == OP_KIND_REDUCE ? 1 + (int32_t)g.others.size() : 1;
-                    if (loads + need > BATCH_MAX_LOADS) break;
-                    loads += need;
-                    e++;
-                }
-                plan->prog.push_back(loads);
-                for (size_t j = q; j < e; j++) {
-                    const Group& g = ops[order_by_level[j].second];
-                    plan->prog.push_back(operand(c, g.anchor));
-                    if (g.kind == OP_KIND_REDUCE) for (int32_t o : g.others) plan->prog.push_back(operand(c, o));
-                }
-                for (size_t j = q; j < e; j++) {
-                    const Group& g = ops[order_by_level[j].second];
-                    const int32_t k = (int32_t)g.others.size();
-                    if (g.kind == OP_KIND_REDUCE) {
-                        plan->prog.push_back(SLOT_START);                       // the destination's own value
-                        for (int32_t i = 0; i + 1 < k; i++) plan->prog.push_back(0);
-                        plan->prog.push_back(0 | (1 << 8));                     // last source, then one store
-                        plan->prog.push_back(operand(c, g.anchor));
-                    } else {
-                        plan->prog.push_back(SLOT_RAW | (k << 8));
-                        for (int32_t o : g.others) plan->prog.push_back(operand(c, o));
-                    }
-                }
-                num_batches++;
-                q = e;
-            }
-        }
-    }
-    plan->chunk_off[(size_t)G] = (int32_t)plan->prog.size();
-    st.num_batches = num_batches;
     return SCCL_OK;
 }

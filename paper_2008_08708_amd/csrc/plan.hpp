@@ -15,20 +15,7 @@
 //   word 2..    : copy: `count` destination operands; reduce: `count` source operands, in schedule order
 // An operand is  rank | slot << 8 : the rank whose buffer is touched and the chunk position of this
 // chunk in that buffer (the chunk id itself under the default layout).
-//
-// Small chunks (one tile per chunk) use a batched form instead, to cut the chain of dependent memory
-// round trips from "one per group" to "one per dependency level": the groups of a chunk are sorted
-// by dependency level and cut into batches of mutually independent groups with at most
-// BATCH_MAX_LOADS loads.  A batch is
-//   word 0          : number of loads n
-//   word 1..n       : the operands to load, value slots 0..n-1
-//   then per slot j : a control word, followed by the operands to store to after this slot
-//                     bit 0 start a new sum with slot j, else add slot j to the running sum
-//                     bit 1 the stores after this slot write slot j's raw bits (a copy group)
-//                     bits 8.. number of stores after this slot (of the running sum unless bit 1)
 constexpr int32_t OP_KIND_REDUCE = 1;
-constexpr int32_t BATCH_MAX_LOADS = 8;
-constexpr int32_t SLOT_START = 1, SLOT_RAW = 2;
 constexpr int32_t OPERAND_RANK_BITS = 8;
 constexpr int32_t OPERAND_RANK_MASK = (1 << OPERAND_RANK_BITS) - 1;
 constexpr int32_t MAX_SLOTS = 1 << (31 - OPERAND_RANK_BITS);
@@ -60,7 +47,6 @@ struct sccl_plan {
     int32_t tiles_per_chunk = 0;
     int64_t num_items = 0;
     int32_t grid = 0;
-    bool batched = false;               // prog holds batches (small-chunk path)
     // device side (owned)
     int device = -1;
     int num_cus = 0;

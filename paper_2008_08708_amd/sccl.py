@@ -24,7 +24,6 @@ SCCL_I32, SCCL_F32, SCCL_F16 = 0, 1, 2
 DTYPE_CODES = {"i32": SCCL_I32, "f32": SCCL_F32, "f16": SCCL_F16}
 SCCL_COPY, SCCL_REDUCE_SUM = 0, 1
 SCCL_PLAN_HOST_ONLY = 1
-SCCL_PLAN_NO_BATCHING = 2
 
 
 class sccl_edge_t(ctypes.Structure):
@@ -71,8 +70,7 @@ class sccl_stats_t(ctypes.Structure):
                 ("bytes_per_rank", ctypes.c_int64), ("bytes_min", ctypes.c_int64),
                 ("bytes_unfused", ctypes.c_int64), ("vector_bytes", ctypes.c_int32),
                 ("block_threads", ctypes.c_int32), ("vectors_per_thread", ctypes.c_int32),
-                ("num_work_items", ctypes.c_int64), ("grid_workgroups", ctypes.c_int32),
-                ("num_batches", ctypes.c_int32)]
+                ("num_work_items", ctypes.c_int64), ("grid_workgroups", ctypes.c_int32)]
 
     def as_dict(self):
         return {name: getattr(self, name) for name, _ in self._fields_}

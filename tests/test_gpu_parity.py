@@ -239,7 +239,7 @@ def test_synthesized_schedules_with_several_rounds_per_step():
             assert (bits(g) == bits(got[0])).all()
 
 
-# ---- the small-chunk path: one workgroup row per chunk, groups issued in batches of independent groups
+# ---- small chunks: a chunk is at most one workgroup row; element counts that force every vector width
 SMALL = []
 for epc in (1, 3, 4, 100, 1000):
     SMALL += [
@@ -248,14 +248,14 @@ for epc in (1, 3, 4, 100, 1000):
         (f"ring8-ar-i32-{epc}", tp.ring(8), 4, "allreduce", "ring", "i32", "u32", epc),
         (f"torus-ag-f32-{epc}", tp.torus2d(4, 4), 4, "allgather", "greedy", "f32", "uniform", epc),
         (f"torus-ar-f16-{epc}", tp.torus2d(4, 4), 2, "allreduce", "greedy", "f16", "normal", epc),
-        (f"K8-ar-f32-{epc}", tp.complete(8), 1, "allreduce", "greedy", "f32", "uniform", epc),      # fan-in 7: 8 loads, one batch
-        (f"K12-ar-f16-{epc}", tp.complete(12), 1, "allreduce", "greedy", "f16", "normal", epc),     # fan-in 11: not batched
+        (f"K8-ar-f32-{epc}", tp.complete(8), 1, "allreduce", "greedy", "f32", "uniform", epc),      # fan-in 7
+        (f"K12-ar-f16-{epc}", tp.complete(12), 1, "allreduce", "greedy", "f16", "normal", epc),     # fan-in 11
         (f"dgx1-rs-f32-{epc}", tp.dgx1(), 2, "reducescatter", "greedy", "f32", "uniform", epc),
     ]
 
 
 @pytest.mark.parametrize("label,topo,C,what,kind,dtype,dist,epc", SMALL, ids=[r[0] for r in SMALL])
-def test_small_chunks_batched_and_unbatched(label, topo, C, what, kind, dtype, dist, epc):
+def test_small_chunks(label, topo, C, what, kind, dtype, dist, epc):
     P = topo.num_nodes
     ag = col.allgather(P, C)
     base = gen.ring_allgather(P, C) if kind == "ring" else gen.greedy_bfs(topo, ag)
@@ -268,21 +268,3 @@ def test_small_chunks_batched_and_unbatched(label, topo, C, what, kind, dtype, d
     bufs = host_inputs(dist, dtype, 71, P, coll.num_chunks, epc, ag.pre if what == "allgather" else None)
     want, got = run_both(topo, coll, sched, dtype, bufs, epc, label=label)
     assert_same_bits(want, got)
-    want, got = run_both(topo, coll, sched, dtype, bufs, epc, label=label + "-unbatched",
-                         options={"flags": sccl.SCCL_PLAN_NO_BATCHING})
-    assert_same_bits(want, got)
-
-
-def test_batched_path_is_taken_for_small_chunks_only():
-    topo = tp.torus2d(4, 4)
-    sched, coll = allreduce_of(topo, 4)
-    p = sccl.sccl_plan_create(*to_binding(topo, coll, sched, "f32", 4))
-    st = sccl.sccl_plan_stats(p)
-    assert st["num_batches"] > 0 and st["num_batches"] < st["num_copy_groups"] + st["num_reduce_groups"]
-    sccl.sccl_plan_destroy(p)
-    p = sccl.sccl_plan_create(*to_binding(topo, coll, sched, "f32", 4), options={"flags": sccl.SCCL_PLAN_NO_BATCHING})
-    assert sccl.sccl_plan_stats(p)["num_batches"] == 0
-    sccl.sccl_plan_destroy(p)
-    p = sccl.sccl_plan_create(*to_binding(topo, coll, sched, "f32", 1 << 16))
-    assert sccl.sccl_plan_stats(p)["num_batches"] == 0
-    sccl.sccl_plan_destroy(p)

@@ -242,23 +242,3 @@ def test_slot_maps_are_validated():
     bad = slot.copy(); bad[held[0], 0] = per_rank
     assert plan_status(topo, coll, s, "f32", 8, slot=bad, slots_per_rank=per_rank)[0] == "SCCL_ERR_INVALID_ARG"
     assert plan_status(topo, coll, s, "f32", 8, slot=slot, slots_per_rank=0)[0] == "SCCL_ERR_INVALID_ARG"
-
-
-def test_small_chunks_are_batched_by_dependency_level():
-    topo = tp.torus2d(4, 4)
-    ag = col.allgather(16, 4)
-    s = gen.greedy_bfs(topo, ag)
-    ar, arc = gen.compose_allreduce(s, ag)
-    _, st = plan_status(topo, arc, ar, "f32", 4)
-    groups = st["num_copy_groups"] + st["num_reduce_groups"]
-    assert 0 < st["num_batches"] < groups
-    # at least one batch per dependency level: a chunk's tree in the torus is at least 2 deep each way
-    assert st["num_batches"] >= 64 * 4
-    _, off = plan_status(topo, arc, ar, "f32", 4, options={"flags": sccl.SCCL_PLAN_HOST_ONLY | sccl.SCCL_PLAN_NO_BATCHING})
-    assert off["num_batches"] == 0
-    # fan-in above 7 does not fit a batch: the ordinary path is used
-    k12 = tp.complete(12)
-    ar12, arc12 = gen.compose_allreduce(gen.greedy_bfs(k12, col.allgather(12, 1)), col.allgather(12, 1))
-    assert plan_status(k12, arc12, ar12, "f32", 4)[1]["num_batches"] == 0
-    # large chunks are not batched
-    assert plan_status(topo, arc, ar, "f32", 1 << 16)[1]["num_batches"] == 0
