@@ -33,6 +33,17 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+def build_probe(verbose: bool = False) -> str:
+    """Compile the standalone bandwidth probe (a measurement aid) next to the library."""
+    out = os.path.join(HERE, "bw_probe")
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           os.path.join(HERE, "csrc", "bw_probe.hip"), "-o", out]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return out
+
+
 def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
@@ -42,3 +53,4 @@ def is_stale() -> bool:
 
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_probe(verbose=True))
