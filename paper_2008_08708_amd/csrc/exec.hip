@@ -4,7 +4,8 @@
 // being usable as soon as the send that produces it is done -- there with a flag per
 // chunk and connection, no global barrier between steps):
 //
-//   * Every rank buffer holds chunk c at the same offset, so the sends of different
+//   * Every rank buffer holds chunk c at one fixed position (by default the same offset in
+//     every buffer), and two chunks never share a position on a rank, so the sends of different
 //     chunks touch disjoint memory, and sends of one chunk act element by element.  The
 //     only order the schedule imposes is therefore, per chunk and per element, the
 //     order of that chunk's sends by step.
