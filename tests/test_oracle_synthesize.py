@@ -110,3 +110,36 @@ def test_synthesized_schedules_compose_into_the_allreduce_rows():
         assert validate(topo, arc, ar).ok
         assert ("allreduce",) + ar.csr(arc.num_chunks) in table
         assert max(ar.rounds) > 1                          # a k > 0 schedule: some step has several rounds
+
+
+def test_shared_constraints_are_respected_by_search_and_generators():
+    # section 3.2.1's shared bus: all pairs may talk, one chunk per round in total.  An Allgather of 4 nodes
+    # moves 12 chunks, one per round: 12 rounds are enough in a single step, 11 are not.
+    bus, ag = tp.shared_bus(4), col.allgather(4, 1)
+    s = syn.solve_instance(bus, ag, 1, 12)
+    assert s is not None and validate(bus, ag, s).ok and s.rounds == [12]
+    assert syn.solve_instance(bus, ag, 1, 11) is None
+    assert syn.solve_instance(bus, ag, 3, 11) is None
+    # the greedy generators spend the shared budget once per send, whatever the link
+    g = gen.greedy_bfs(bus, ag, rounds=[3] * 8)
+    assert validate(bus, ag, g).ok and g.num_rounds >= 12
+    # the model of section 5.2.2: two fully connected islands whose bridge nodes share one bus per side
+    links = {}
+    for isl in ((0, 2, 3), (4, 6, 7)):
+        for a in isl:
+            for b in isl:
+                if a != b:
+                    links[(a, b)] = 1
+    bw = [(frozenset([e]), b) for e, b in links.items()]
+    left = frozenset([(0, 1), (1, 0), (1, 2), (2, 1), (1, 3), (3, 1)])          # the paper's left-socket entry
+    right = frozenset([(4, 5), (5, 4), (5, 6), (6, 5), (5, 7), (7, 5)])
+    bridge = frozenset([(1, 5)]), frozenset([(5, 1)])
+    topo = tp.Topology(8, tuple(bw) + ((left, 1), (right, 1), (bridge[0], 1), (bridge[1], 1)), "z52-pcie")
+    ag8 = col.allgather(8, 1)
+    g = gen.greedy_bfs(topo, ag8)
+    rep = validate(topo, ag8, g)
+    assert rep.ok, rep.detail
+    # everything the right half learns about the left half crosses 1 -> 5, one chunk per round: at least 4 rounds
+    assert g.num_rounds >= 4 and g.num_steps >= tp.diameter(topo)
+    exact = syn.solve_instance(topo, ag8, g.num_steps, g.num_rounds)
+    assert exact is not None and validate(topo, ag8, exact).ok
