@@ -162,6 +162,7 @@ def main():
     ap.add_argument("--block-threads", type=int, default=0)
     ap.add_argument("--vectors-per-thread", type=int, default=0)
     ap.add_argument("--max-workgroups", type=int, default=0)
+    ap.add_argument("--lowering", type=int, default=0, help="0 = the plan chooses, 1 = through memory, 2 = staged in the local data share")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", default="", metavar="FILE", help="also time the other configurations; markdown table to FILE")
     args = ap.parse_args()
@@ -178,7 +179,7 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     options = {k: v for k, v in (("block_threads", args.block_threads), ("vectors_per_thread", args.vectors_per_thread),
-                                 ("max_workgroups", args.max_workgroups)) if v}
+                                 ("max_workgroups", args.max_workgroups), ("lowering", args.lowering)) if v}
     if args.workload.startswith("cfg5:"):             # cfg5:<allgather|allreduce>:<bytes per rank>
         _, coll_name, size = args.workload.split(":")
         wl = workloads.sweep_workload(coll_name, int(size))
@@ -208,7 +209,7 @@ def main():
                      "frac": round(gbs / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC.get((args.workload, st["grid_workgroups"], st["block_threads"],
                                                       st["vectors_per_thread"])),
-                     "kernel": "sccl_exec_kernel (one launch = the whole schedule)",
+                     "kernel": ("sccl_staged_kernel" if st["lowering"] == 2 else "sccl_exec_kernel") + " (one launch = the whole schedule)",
                      "algorithmic_bytes_per_launch": st["bytes_min"]},
     }
     try:
@@ -232,8 +233,10 @@ def main():
         for coll in ("allgather", "allreduce"):
             for size in workloads.sweep_sizes():
                 names.append((f"cfg5 {coll} {size}", workloads.sweep_workload(coll, size)))
-        def median_us(w, steps, mode):
-            r = time_workload(w, steps, 3, mode=mode)
+        from paper_2008_08708_amd.sccl import SCCL_LOWER_MEMORY, SCCL_LOWER_STAGED, ScclError
+
+        def median_us(w, steps, mode, opts=None):
+            r = time_workload(w, steps, 3, options=opts, mode=mode)
             m = sorted(r["ms"])
             out = (m[len(m) // 2] * 1e3, m[0] * 1e3, r["stats"])
             del r
@@ -242,23 +245,35 @@ def main():
 
         for label, w in names:
             steps = 5 if w.bytes_per_rank >= (1 << 30) else 20
-            med, mn, s = median_us(w, steps, "sccl_execute")
+            med, mn, s = median_us(w, steps, "sccl_execute")                     # the default: lowering chosen by the plan
+            mem_med = med if s["lowering"] == SCCL_LOWER_MEMORY else median_us(w, steps, "sccl_execute", {"lowering": SCCL_LOWER_MEMORY})[0]
+            stg_med = None
+            if s["lowering"] == SCCL_LOWER_STAGED:
+                stg_med = med
+            elif s["staged_available"] and w.bytes_per_rank <= (16 << 20):
+                try:
+                    stg_med = median_us(w, steps, "sccl_execute", {"lowering": SCCL_LOWER_STAGED})[0]
+                except ScclError:
+                    stg_med = None
             step_med, _, _ = median_us(w, steps, "sccl_execute_stepwise")
             cpy_med = median_us(w, steps, "sccl_execute_memcpy")[0] if s["num_reduce_groups"] == 0 else None
             rows.append((label, s["num_nodes"], w.bytes_per_rank, s["chunk_bytes"], s["num_steps"], s["bytes_min"],
-                         med, mn, s["bytes_min"] / (med * 1e-6) / 1e9, s["block_threads"],
-                         s["vectors_per_thread"], s["grid_workgroups"], step_med, cpy_med))
-            print(f"[report] {label}: fused {med:.1f} us ({rows[-1][8]:.1f} GB/s), per-step kernels {step_med:.1f} us, "
-                  f"per-send copies {cpy_med if cpy_med is None else round(cpy_med, 1)} us", file=sys.stderr, flush=True)
+                         med, mn, s["bytes_min"] / (med * 1e-6) / 1e9, "staged" if s["lowering"] == SCCL_LOWER_STAGED else "memory",
+                         s["num_levels"], s["grid_workgroups"], mem_med, stg_med, step_med, cpy_med))
+            fmt = lambda x: "-" if x is None else format(x, ".1f")
+            print(f"[report] {label}: default ({rows[-1][9]}) {med:.1f} us ({rows[-1][8]:.1f} GB/s), through memory {fmt(mem_med)} us, "
+                  f"staged {fmt(stg_med)} us, per-step kernels {fmt(step_med)} us, per-send copies {fmt(cpy_med)} us",
+                  file=sys.stderr, flush=True)
         os.makedirs(os.path.dirname(os.path.abspath(args.report)), exist_ok=True)
         with open(args.report, "w") as f:
-            f.write("| workload | P | bytes/rank | chunk bytes | S | bytes_min | fused: median us | min us | effective GB/s | % of 8 TB/s "
-                    "| block | vec/lane | grid | one kernel per step: us | one copy per send: us |\n")
-            f.write("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|\n")
+            f.write("| workload | P | bytes/rank | chunk bytes | S | bytes_min | sccl_execute: median us | min us | effective GB/s | % of 8 TB/s "
+                    "| lowering | levels | grid | through memory: us | staged: us | one kernel per step: us | one copy per send: us |\n")
+            f.write("|" + "---|" * 17 + "\n")
+            fmt = lambda x: "-" if x is None else format(x, ".1f")
             for r in rows:
                 f.write(f"| {r[0]} | {r[1]} | {r[2]} | {r[3]} | {r[4]} | {r[5]} | {r[6]:.1f} | {r[7]:.1f} | {r[8]:.1f} | "
-                        f"{100 * r[8] / HBM_PEAK_GBS:.1f} | {r[9]} | {r[10]} | {r[11]} | {r[12]:.1f} | "
-                        f"{'-' if r[13] is None else format(r[13], '.1f')} |\n")
+                        f"{100 * r[8] / HBM_PEAK_GBS:.1f} | {r[9]} | {r[10]} | {r[11]} | {fmt(r[12])} | {fmt(r[13])} | "
+                        f"{fmt(r[14])} | {fmt(r[15])} |\n")
     print(json.dumps(line), flush=True)
 
 

@@ -123,12 +123,35 @@ typedef struct {
 
 /* Options of sccl_plan_create_ex; zero-initialise for the defaults. */
 #define SCCL_PLAN_HOST_ONLY 1u     /* validate and compile only: touches no device; the plan cannot be executed */
+
+/* How sccl_execute lowers the plan (paper, section 4: the same schedule admits several lowerings).
+ *   SCCL_LOWER_MEMORY  every send reads and writes the rank buffers; what one step wrote the next step
+ *                      reads back through the cache hierarchy.  Work is split by (chunk, element tile).
+ *   SCCL_LOWER_STAGED  a workgroup takes one element slice of EVERY chunk of EVERY rank, loads the cells
+ *                      (rank, chunk position) the schedule reads into the local data share, runs all
+ *                      sends there, dependency level by dependency level, and writes the cells the
+ *                      schedule wrote back once.  Same operations in the same order per element, hence
+ *                      the same bits; made for small buffers, where the time is the chain of memory
+ *                      round trips (the latency term of the paper's cost model, section 3.6) and not the
+ *                      bytes.  Needs room for one slice of every cell: SCCL_ERR_INVALID_ARG if asked
+ *                      for explicitly and the cells do not fit.
+ *   SCCL_LOWER_AUTO    staged when the cells fit and the P rank buffers together are at most 512 KiB
+ *                      (the measured crossover: below it the time is launch plus latency and no
+ *                      bandwidth claim applies), through memory otherwise. */
+#define SCCL_LOWER_AUTO   0
+#define SCCL_LOWER_MEMORY 1
+#define SCCL_LOWER_STAGED 2
+
 typedef struct {
     uint32_t flags;
-    int32_t block_threads;         /* 0 = choose from the chunk size; else 64, 128 or 256 */
-    int32_t vectors_per_thread;    /* 0 = choose; else 1, 2, 4 or 8: vectors each lane moves per operand */
-    int32_t max_workgroups;        /* 0 = one workgroup per compute unit; else the grid size;
-                                      either way capped by the number of work items */
+    int32_t block_threads;         /* through-memory kernel: 0 = choose from the chunk size; else 64, 128 or 256 */
+    int32_t vectors_per_thread;    /* through-memory kernel: 0 = choose; else 1, 2, 4 or 8 vectors per lane and operand */
+    int32_t max_workgroups;        /* 0 = choose (through memory: one workgroup per compute unit); else the
+                                      grid size of either kernel; always capped by the number of work items */
+    int32_t lowering;              /* SCCL_LOWER_* */
+    int32_t slice_vectors;         /* staged kernel: 0 = choose; else a power of two: vectors of every cell a
+                                      workgroup stages at a time */
+    int32_t staged_threads;        /* staged kernel: 0 = choose; else 64, 128, 256, 512 or 1024 */
     int32_t reserved;              /* must be 0 */
 } sccl_options_t;
 
@@ -149,7 +172,18 @@ typedef struct {
     int32_t vector_bytes;          /* 16, 8, 4 or 2: widest access that divides the chunk size */
     int32_t block_threads, vectors_per_thread;
     int64_t num_work_items;        /* G * tiles per chunk */
-    int32_t grid_workgroups;       /* 0 for a host-only plan */
+    int32_t grid_workgroups;       /* grid of the kernel sccl_execute launches; 0 for a host-only plan */
+    /* the staged lowering: dependency structure of the schedule and what a workgroup stages */
+    int32_t lowering;              /* SCCL_LOWER_MEMORY or SCCL_LOWER_STAGED: what sccl_execute runs */
+    int32_t staged_available;      /* 1 if one slice of every cell fits the local data share */
+    int32_t num_cells;             /* distinct (rank, chunk position) pairs some send touches */
+    int32_t num_cells_loaded;      /* of those, read before any send writes them */
+    int32_t num_cells_stored;      /* of those, written by some send */
+    int32_t num_levels;            /* length of the longest chain of dependent groups */
+    int32_t max_level_tasks;       /* most cell writes any one level performs */
+    int32_t slice_vectors, staged_threads;
+    int32_t staged_lds_bytes;      /* local data share one workgroup uses */
+    int64_t num_slices;            /* staged work items: ceil(vectors per chunk / slice_vectors) */
 } sccl_stats_t;
 
 typedef struct sccl_plan sccl_plan_t;
@@ -175,8 +209,9 @@ sccl_status_t sccl_plan_create_ex(const sccl_topology_t* topology, const sccl_co
  * kernel as in section 4, "single kernel") on the P device buffers
  * rank_buffers[0..P-1], each G (or slots_per_rank) * elems_per_chunk elements, 16-byte aligned and
  * pairwise disjoint (checked: SCCL_ERR_ALIGNMENT / SCCL_ERR_OVERLAP).
- * `stream` is a hipStream_t (NULL = the default stream).  The call enqueues
- * one kernel and returns; it does not synchronise and does not allocate.  The
+ * `stream` is a hipStream_t (NULL = the default stream).  Which kernel runs is
+ * the plan's lowering (sccl_options_t.lowering, reported by sccl_plan_stats).
+ * The call enqueues one kernel and returns; it does not synchronise and does not allocate.  The
  * pointer array is read on the host during the call.  Nothing is launched
  * when the status is not SCCL_OK.  A plan is immutable: concurrent calls with
  * one plan are allowed as long as their buffers differ.

@@ -26,6 +26,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
 #include <cstring>
 #include <new>
@@ -328,6 +329,216 @@ __global__ void __launch_bounds__(256) copy16_kernel(u32x4* __restrict__ dst, co
     for (size_t i = full * tile + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+
+// ---- the staged lowering -----------------------------------------------------------------------
+// A work item is an element *slice*: the same `slice` vectors of every chunk of every rank.  The
+// workgroup (1) loads the slice of every cell the schedule reads before writing into the local data
+// share, all loads in flight together: one memory round trip; (2) runs the schedule there, one
+// dependency level after the other with a workgroup barrier in between, one lane per (cell write,
+// vector); (3) stores the slice of every cell the schedule wrote.  Per element the operations and their
+// order are those of the schedule, so the bits equal the other lowerings'.  The chain of a chunk's
+// sends costs local-memory latency per level instead of a cache round trip per group, which is what
+// small buffers are bound by.
+struct StagedArgs {
+    const int32_t* table;         // see plan.hpp
+    int64_t chunk_bytes;
+    int64_t num_slices;
+    int64_t vecs_per_chunk;
+    int32_t n_in, n_out, n_levels, table_words;
+    int32_t off_out, off_lev, off_task, off_srcs;
+    int32_t log_slice;            // vectors per slice = 1 << log_slice
+    int32_t max_level_tasks;      // tasks of the widest level
+    char* bufs[SCCL_MAX_RANKS];
+};
+
+// Base pointer of rank `rank` (any value per lane) out of the wavefront's copy: lane n holds bufs[n].
+__device__ __forceinline__ char* rank_base(uint32_t lo, uint32_t hi, int32_t rank) {
+    const uint32_t l = (uint32_t)__shfl((int)lo, rank, 64), h = (uint32_t)__shfl((int)hi, rank, 64);
+    return (char*)(((uint64_t)h << 32) | l);
+}
+
+// One task as a lane holds it: the two table words (t0 < 0: no task) and, for a reduce task, its
+// first four source cells.
+struct StagedTask { int32_t t0, t1, s[4]; };
+
+__device__ __forceinline__ void fetch_words(StagedTask& t, const int32_t* tab, const StagedArgs& a,
+                                            int32_t t_lo, int32_t t_hi, int32_t i, int32_t ls) {
+    const int32_t task = t_lo + (i >> ls);
+    t.t0 = -1; t.t1 = 0;
+    if (task < t_hi) {
+        t.t0 = tab[a.off_task + 2 * task];
+        t.t1 = tab[a.off_task + 2 * task + 1];
+    }
+}
+__device__ __forceinline__ void fetch_sources(StagedTask& t, const int32_t* tab, const StagedArgs& a) {
+    if (t.t0 >= (1 << 16)) {                                       // a reduce task; the list is padded by three words
+#pragma unroll
+        for (int j = 0; j < 4; j++) t.s[j] = tab[a.off_srcs + t.t1 + j];
+    }
+}
+
+template <int DT, int W>
+__device__ __forceinline__ void run_task(typename VecOf<W>::type* cells, const int32_t* tab, const StagedArgs& a,
+                                         const StagedTask& t, int32_t v, int32_t ls) {
+    typedef typename VecOf<W>::type V;
+    if (t.t0 < 0) return;
+    const int32_t dst = t.t0 & 0xffff, k = t.t0 >> 16;
+    if (k == 0) {
+        cells[(dst << ls) + v] = cells[(t.t1 << ls) + v];
+        return;
+    }
+    // the destination's own value first, then the sources in schedule order
+    V x[4];
+    const V d = cells[(dst << ls) + v];
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+        if (j < k) x[j] = cells[(t.s[j] << ls) + v];
+    Acc<DT, W> acc;
+    acc.init(d);
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+        if (j < k) acc.add(x[j]);
+    for (int32_t j = 4; j < k; j++) acc.add(cells[(tab[a.off_srcs + t.t1 + j] << ls) + v]);
+    cells[(dst << ls) + v] = acc.template done<V>();
+}
+
+// First task of level l (any l >= 0; beyond the last level: the end) out of the wavefront's copy of the
+// level table: lane n holds entries n, n + 64, n + 128, n + 192.  l is the same in every lane.
+__device__ __forceinline__ int32_t level_first(const int32_t (&reg)[4], int32_t l, int32_t n_levels) {
+    l = l < n_levels ? l : n_levels;
+    const int32_t q = l >> 6;
+    const int32_t r = q == 0 ? reg[0] : q == 1 ? reg[1] : q == 2 ? reg[2] : reg[3];
+    return __builtin_amdgcn_readlane(r, l & 63);
+}
+
+template <int DT, int W>
+__global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
+    typedef typename VecOf<W>::type V;
+    extern __shared__ __attribute__((aligned(16))) unsigned char staged_lds[];
+    const int32_t* tab = (const int32_t*)staged_lds;
+    V* cells = (V*)(staged_lds + (size_t)a.table_words * 4);      // table_words is a multiple of 4
+    const int32_t tid = (int32_t)threadIdx.x, BT = (int32_t)blockDim.x;
+    const int32_t ls = a.log_slice, sv = 1 << ls, vmask = sv - 1;
+
+    // lane n of every wavefront keeps the base pointer of rank n (P <= 64 = lanes of a wavefront) ...
+    const uint64_t mine = (uint64_t)a.bufs[tid & 63];
+    const uint32_t base_lo = (uint32_t)mine, base_hi = (uint32_t)(mine >> 32);
+    // ... and the level table (at most 256 entries), so that level bounds cost no memory access
+    int32_t levreg[4];
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int32_t l = (tid & 63) + 64 * q;
+        levreg[q] = a.table[a.off_lev + (l < a.n_levels ? l : a.n_levels)];
+    }
+
+    // the tables go to the local data share once per workgroup, 16 bytes per lane and trip
+    {
+        const u32x4* src = (const u32x4*)a.table;
+        u32x4* dst = (u32x4*)staged_lds;
+        for (int32_t i = tid; i < a.table_words / 4; i += BT) dst[i] = src[i];
+    }
+
+    constexpr int UA = 4;                                          // loads a lane keeps in flight in phase 1
+    const int32_t in_lanes = a.n_in << ls, out_lanes = a.n_out << ls;
+    for (int64_t slice = blockIdx.x; slice < a.num_slices; slice += gridDim.x) {
+        const int64_t v0 = slice << ls;
+        const int64_t left = a.vecs_per_chunk - v0;
+        const int32_t here = left < sv ? (int32_t)left : sv;       // vectors of this slice that exist
+        const int64_t slice_off = v0 * W;
+        const bool live = (tid & vmask) < here;                    // this lane's vector exists in this slice
+
+        // ---- (1) load: cell i < n_in is the i-th loaded cell; its operand word comes straight from memory
+        for (int32_t base = 0; base < in_lanes; base += BT * UA) {
+            int32_t w[UA]; bool ok[UA]; V x[UA];
+#pragma unroll
+            for (int u = 0; u < UA; u++) {
+                const int32_t i = base + u * BT + tid;
+                ok[u] = i < in_lanes && (i & vmask) < here;
+                w[u] = ok[u] ? a.table[i >> ls] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < UA; u++) {
+                const int32_t i = base + u * BT + tid;
+                char* p = rank_base(base_lo, base_hi, w[u] & OPERAND_RANK_MASK) +
+                          (int64_t)(w[u] >> OPERAND_RANK_BITS) * a.chunk_bytes + slice_off + (int64_t)(i & vmask) * W;
+                if (ok[u]) x[u] = *(const V*)p;
+            }
+#pragma unroll
+            for (int u = 0; u < UA; u++) {
+                const int32_t i = base + u * BT + tid;
+                if (ok[u]) cells[i] = x[u];                        // cell (i >> ls), vector (i & vmask)
+            }
+        }
+        __syncthreads();
+
+        // ---- (2) the schedule, level by level.  The tables are read-only, so a lane fetches its task of the
+        // NEXT level (two words, then a reduce task's sources) while the cells of the current level are on
+        // their way; wavefronts beyond the widest level only take part in the barriers.
+        // The first cell this lane stores in phase 3, (cell id, operand word), is fetched here as well.
+        const bool ok0 = tid < out_lanes && live;
+        const int32_t out_c0 = ok0 ? tab[a.off_out + 2 * (tid >> ls)] : 0;
+        const int32_t out_w0 = ok0 ? tab[a.off_out + 2 * (tid >> ls) + 1] : 0;
+        const bool wave_works = (tid & ~63) < (a.max_level_tasks << ls);      // the same in every lane of a wavefront
+        int32_t lo0 = level_first(levreg, 0, a.n_levels), lo1 = level_first(levreg, 1, a.n_levels);
+        StagedTask cur;
+        if (wave_works) {
+            fetch_words(cur, tab, a, lo0, lo1, tid, ls);
+            fetch_sources(cur, tab, a);
+        }
+        for (int32_t lv = 0; lv < a.n_levels; lv++) {
+            const int32_t lo2 = level_first(levreg, lv + 2, a.n_levels);
+            if (wave_works) {
+                StagedTask nxt;
+                fetch_words(nxt, tab, a, lo1, lo2, tid, ls);
+                if (live) run_task<DT, W>(cells, tab, a, cur, tid & vmask, ls);
+                fetch_sources(nxt, tab, a);
+                const int32_t lanes = (lo1 - lo0) << ls;
+                for (int32_t i = tid + BT; i < lanes; i += BT) {   // levels wider than the workgroup
+                    if ((i & vmask) >= here) continue;
+                    StagedTask t;
+                    fetch_words(t, tab, a, lo0, lo1, i, ls);
+                    fetch_sources(t, tab, a);
+                    run_task<DT, W>(cells, tab, a, t, i & vmask, ls);
+                }
+                cur = nxt;
+            }
+            __syncthreads();
+            lo0 = lo1; lo1 = lo2;
+        }
+
+        // ---- (3) store every cell the schedule wrote
+        for (int32_t base = 0; base < out_lanes; base += BT) {
+            const int32_t i = base + tid;
+            const bool ok = i < out_lanes && (i & vmask) < here;
+            const int32_t c = base == 0 ? out_c0 : (ok ? tab[a.off_out + 2 * (i >> ls)] : 0);
+            const int32_t w = base == 0 ? out_w0 : (ok ? tab[a.off_out + 2 * (i >> ls) + 1] : 0);
+            char* p = rank_base(base_lo, base_hi, w & OPERAND_RANK_MASK) +
+                      (int64_t)(w >> OPERAND_RANK_BITS) * a.chunk_bytes + slice_off + (int64_t)(i & vmask) * W;
+            if (ok) *(V*)p = cells[(c << ls) + (i & vmask)];
+        }
+        if (slice + gridDim.x < a.num_slices) __syncthreads();     // the next slice overwrites the cells
+    }
+}
+
+typedef void (*staged_fn)(const StagedArgs);
+template <int DT>
+staged_fn pick_staged_w(int W) {
+    switch (W) {
+        case 16: return sccl_staged_kernel<DT, 16>;
+        case 8:  return sccl_staged_kernel<DT, 8>;
+        default: return sccl_staged_kernel<DT, 4>;
+    }
+}
+staged_fn pick_staged_kernel(sccl_dtype_t dt, int W) {
+    switch (dt) {
+        case SCCL_I32: return pick_staged_w<SCCL_I32>(W);
+        case SCCL_F32: return pick_staged_w<SCCL_F32>(W);
+        default:
+            if (W == 2) return sccl_staged_kernel<SCCL_F16, 2>;
+            return pick_staged_w<SCCL_F16>(W);
+    }
+}
+
 typedef void (*kernel_fn)(const ExecArgs);
 typedef void (*step_kernel_fn)(const StepArgs);
 
@@ -430,13 +641,30 @@ sccl_status_t sccl_plan_create_ex(const sccl_topology_t* topology, const sccl_co
                     (pb == 0 || hipMemcpy(plan->d_prog, plan->prog.data(), pb, hipMemcpyHostToDevice) == hipSuccess) &&
                     hipMemcpy(plan->d_chunk_off, plan->chunk_off.data(), ob, hipMemcpyHostToDevice) == hipSuccess;
         if (!good) { sccl_plan_destroy(plan); return SCCL_ERR_DEVICE; }
+        sccl_staged& sg = plan->staged;
+        if (sg.available) {
+            const size_t tb = sg.table.size() * sizeof(int32_t);
+            staged_fn sfn = pick_staged_kernel(plan->dtype, plan->vector_bytes);
+            // more than 64 KiB of dynamic local data share has to be asked for, per kernel
+            const bool staged_ok =
+                hipFuncSetAttribute((const void*)sfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)STAGED_LDS_LIMIT) == hipSuccess &&
+                hipMalloc((void**)&plan->d_staged, tb) == hipSuccess &&
+                hipMemcpy(plan->d_staged, sg.table.data(), tb, hipMemcpyHostToDevice) == hipSuccess;
+            if (!staged_ok) { sccl_plan_destroy(plan); return SCCL_ERR_DEVICE; }
+            // as many workgroups per CU as its local data share and its 2048 lanes hold, at most 8
+            int64_t per_cu = std::min<int64_t>(STAGED_LDS_LIMIT / sg.lds_bytes, 2048 / sg.threads);
+            per_cu = std::max<int64_t>(1, std::min<int64_t>(per_cu, 8));
+            int64_t sgrid = plan->opts.max_workgroups > 0 ? plan->opts.max_workgroups : num_cus * per_cu;
+            if (sgrid > sg.num_slices) sgrid = sg.num_slices;
+            sg.grid = (int32_t)sgrid;
+        }
         // One persistent workgroup per CU: measured best, because fewer tiles in flight means the
         // values a lane wrote in one step are still in the L2 when it reads them in the next.
         int64_t grid = num_cus;
         if (plan->opts.max_workgroups > 0) grid = plan->opts.max_workgroups;
         if (grid > plan->num_items) grid = plan->num_items;
         plan->grid = (int32_t)grid;
-        plan->stats.grid_workgroups = plan->grid;
+        plan->stats.grid_workgroups = plan->lowering == SCCL_LOWER_STAGED ? sg.grid : plan->grid;
     }
     *out_plan = plan;
     return SCCL_OK;
@@ -503,11 +731,31 @@ sccl_status_t sccl_execute_memcpy(const sccl_plan_t* plan, void* const* rank_buf
     return SCCL_OK;
 }
 
+static sccl_status_t launch_staged(const sccl_plan_t* plan, void* const* rank_buffers, void* stream) {
+    const sccl_staged& sg = plan->staged;
+    StagedArgs args;
+    std::memset(&args, 0, sizeof(args));
+    args.table = plan->d_staged;
+    args.chunk_bytes = plan->stats.chunk_bytes;
+    args.num_slices = sg.num_slices;
+    args.vecs_per_chunk = plan->vecs_per_chunk;
+    args.n_in = sg.n_in; args.n_out = sg.n_out; args.n_levels = sg.n_levels;
+    args.table_words = (int32_t)sg.table.size();
+    args.off_out = sg.off_out; args.off_lev = sg.off_lev; args.off_task = sg.off_task; args.off_srcs = sg.off_srcs;
+    args.log_slice = sg.log_slice_vectors;
+    args.max_level_tasks = sg.max_level_tasks;
+    for (int32_t n = 0; n < plan->P; n++) args.bufs[n] = (char*)rank_buffers[n];
+    staged_fn fn = pick_staged_kernel(plan->dtype, plan->vector_bytes);
+    hipLaunchKernelGGL(fn, dim3((unsigned)sg.grid), dim3((unsigned)sg.threads), (size_t)sg.lds_bytes, (hipStream_t)stream, args);
+    return hipGetLastError() == hipSuccess ? SCCL_OK : SCCL_ERR_DEVICE;
+}
+
 sccl_status_t sccl_execute(const sccl_plan_t* plan, void* const* rank_buffers, void* stream) {
     const sccl_status_t chk = check_buffers(plan, rank_buffers);
     if (chk != SCCL_OK) return chk;
     const int32_t P = plan->P;
     if (plan->num_items == 0 || plan->prog.empty()) return SCCL_OK;     // nothing to move
+    if (plan->lowering == SCCL_LOWER_STAGED) return launch_staged(plan, rank_buffers, stream);
     ExecArgs args;
     std::memset(&args, 0, sizeof(args));
     args.prog = plan->d_prog;
@@ -533,6 +781,7 @@ void sccl_plan_destroy(sccl_plan_t* plan) {
     if (plan->d_chunk_off) (void)hipFree(plan->d_chunk_off);
     if (plan->d_step_prog) (void)hipFree(plan->d_step_prog);
     if (plan->d_group_off) (void)hipFree(plan->d_group_off);
+    if (plan->d_staged) (void)hipFree(plan->d_staged);
     delete plan;
 }
 

@@ -28,6 +28,109 @@ struct Group {
 
 int elem_bytes(sccl_dtype_t d) { return d == SCCL_F16 ? 2 : 4; }
 
+// Tables of the staged lowering from the groups in step order (plan->step_prog): cells, levels, tasks.
+// Returns false when the schedule has more cells than a task word can name.
+bool build_staged_tables(const sccl_plan& plan, sccl_staged* out) {
+    sccl_staged& sg = *out;
+    sg = sccl_staged();
+    const std::vector<int32_t>& prog = plan.step_prog;
+    const size_t n_groups = plan.group_off.size();
+    // pass 1: the cells, and which of them are read before they are written
+    std::map<int32_t, int32_t> first_access;              // operand word -> 0 read first, 1 written first
+    std::vector<int32_t> order;                           // operand words by first appearance
+    auto touch = [&](int32_t w, int32_t how) {
+        if (first_access.emplace(w, how).second) order.push_back(w);
+    };
+    for (size_t g = 0; g < n_groups; g++) {
+        const int32_t* op = &prog[(size_t)plan.group_off[g]];
+        const int32_t k = op[0] >> 8;
+        if (op[0] & OP_KIND_REDUCE) {
+            touch(op[1], 0);                              // the destination's own value is the first operand
+            for (int32_t j = 0; j < k; j++) touch(op[2 + j], 0);
+        } else {
+            touch(op[1], 0);
+            for (int32_t j = 0; j < k; j++) touch(op[2 + j], 1);
+        }
+    }
+    if (order.size() >= (size_t)STAGED_MAX_CELLS) return false;
+    std::map<int32_t, int32_t> cell;                      // operand word -> cell id, loaded cells first
+    std::vector<int32_t> cell_word;
+    for (int pass = 0; pass < 2; pass++)
+        for (int32_t w : order)
+            if (first_access[w] == pass) { cell[w] = (int32_t)cell_word.size(); cell_word.push_back(w); }
+    sg.n_cells = (int32_t)cell_word.size();
+    for (int32_t w : order) sg.n_in += first_access[w] == 0;
+
+    // pass 2: levels.  wl/rl: level of the last write of a cell / highest level that read it.
+    std::vector<int32_t> wl((size_t)sg.n_cells, 0), rl((size_t)sg.n_cells, 0), level(n_groups, 0);
+    std::vector<uint8_t> written((size_t)sg.n_cells, 0);
+    int32_t n_levels = 0;
+    for (size_t g = 0; g < n_groups; g++) {
+        const int32_t* op = &prog[(size_t)plan.group_off[g]];
+        const int32_t k = op[0] >> 8;
+        const bool reduce = (op[0] & OP_KIND_REDUCE) != 0;
+        const int32_t anchor = cell[op[1]];
+        int32_t lv = 1;
+        if (reduce) {
+            // reads the destination and the sources, writes the destination (its own read is no conflict)
+            lv = std::max(lv, std::max(wl[(size_t)anchor], rl[(size_t)anchor]) + 1);
+            for (int32_t j = 0; j < k; j++) lv = std::max(lv, wl[(size_t)cell[op[2 + j]]] + 1);
+        } else {
+            lv = std::max(lv, wl[(size_t)anchor] + 1);
+            for (int32_t j = 0; j < k; j++) {
+                const int32_t d = cell[op[2 + j]];
+                lv = std::max(lv, std::max(wl[(size_t)d], rl[(size_t)d]) + 1);
+            }
+        }
+        level[g] = lv;
+        n_levels = std::max(n_levels, lv);
+        if (reduce) {
+            for (int32_t j = 0; j < k; j++) { int32_t& r = rl[(size_t)cell[op[2 + j]]]; r = std::max(r, lv); }
+            wl[(size_t)anchor] = lv; written[(size_t)anchor] = 1;
+        } else {
+            rl[(size_t)anchor] = std::max(rl[(size_t)anchor], lv);
+            for (int32_t j = 0; j < k; j++) { const int32_t d = cell[op[2 + j]]; wl[(size_t)d] = lv; written[(size_t)d] = 1; }
+        }
+    }
+    sg.n_levels = n_levels;
+
+    // pass 3: the tasks, level by level, groups in step order inside a level
+    std::vector<int32_t> out_cells, lev_first((size_t)n_levels + 1, 0), tasks, srcs;
+    for (int32_t c = 0; c < sg.n_cells; c++)
+        if (written[(size_t)c]) { out_cells.push_back(c); out_cells.push_back(cell_word[(size_t)c]); }
+    for (int32_t lv = 1; lv <= n_levels; lv++) {
+        lev_first[(size_t)lv - 1] = (int32_t)(tasks.size() / 2);
+        for (size_t g = 0; g < n_groups; g++) {
+            if (level[g] != lv) continue;
+            const int32_t* op = &prog[(size_t)plan.group_off[g]];
+            const int32_t k = op[0] >> 8;
+            if (op[0] & OP_KIND_REDUCE) {
+                tasks.push_back(cell[op[1]] | (k << 16));
+                tasks.push_back((int32_t)srcs.size());
+                for (int32_t j = 0; j < k; j++) srcs.push_back(cell[op[2 + j]]);
+            } else {
+                for (int32_t j = 0; j < k; j++) { tasks.push_back(cell[op[2 + j]]); tasks.push_back(cell[op[1]]); }
+            }
+        }
+        sg.max_level_tasks = std::max(sg.max_level_tasks, (int32_t)(tasks.size() / 2) - lev_first[(size_t)lv - 1]);
+    }
+    lev_first[(size_t)n_levels] = (int32_t)(tasks.size() / 2);
+    sg.n_tasks = (int32_t)(tasks.size() / 2);
+    lev_first.push_back(lev_first.back());                // the kernel reads one level ahead
+    srcs.insert(srcs.end(), 3, 0);                        // and four sources at a time
+    sg.n_out = (int32_t)(out_cells.size() / 2);
+    sg.table = cell_word;
+    sg.off_out = (int32_t)sg.table.size();  sg.table.insert(sg.table.end(), out_cells.begin(), out_cells.end());
+    sg.off_lev = (int32_t)sg.table.size();  sg.table.insert(sg.table.end(), lev_first.begin(), lev_first.end());
+    sg.off_task = (int32_t)sg.table.size(); sg.table.insert(sg.table.end(), tasks.begin(), tasks.end());
+    sg.off_srcs = (int32_t)sg.table.size(); sg.table.insert(sg.table.end(), srcs.begin(), srcs.end());
+    while (sg.table.size() % 4) sg.table.push_back(0);   // whole 16-byte vectors
+    return true;
+}
+
+int32_t pow2_at_least(int64_t x) { int32_t p = 1; while (p < x && p < (1 << 30)) p <<= 1; return p; }
+int32_t log2_of(int32_t p) { int32_t l = 0; while ((1 << l) < p) l++; return l; }
+
 }  // namespace
 
 sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collective_t* coll,
@@ -48,6 +151,12 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
         if (!(bt == 0 || bt == 64 || bt == 128 || bt == 256)) return SCCL_ERR_INVALID_ARG;
         if (!(vt == 0 || vt == 1 || vt == 2 || vt == 4 || vt == 8)) return SCCL_ERR_INVALID_ARG;
         if (opts->max_workgroups < 0) return SCCL_ERR_INVALID_ARG;
+        if (opts->lowering != SCCL_LOWER_AUTO && opts->lowering != SCCL_LOWER_MEMORY && opts->lowering != SCCL_LOWER_STAGED)
+            return SCCL_ERR_INVALID_ARG;
+        const int32_t sv = opts->slice_vectors, sth = opts->staged_threads;
+        if (sv < 0 || sv > (1 << 20) || (sv & (sv - 1))) return SCCL_ERR_INVALID_ARG;
+        if (!(sth == 0 || sth == 64 || sth == 128 || sth == 256 || sth == 512 || sth == 1024)) return SCCL_ERR_INVALID_ARG;
+        if (opts->reserved != 0) return SCCL_ERR_INVALID_ARG;
     }
     int64_t R = 0;
     for (int32_t s = 0; s < S; s++) {
@@ -307,5 +416,49 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
     st.vectors_per_thread = vt;
     st.num_work_items = plan->num_items;
     st.grid_workgroups = 0;
+
+    // ---- the staged lowering: tables, then the slice a workgroup stages at a time
+    sccl_staged& sg = plan->staged;
+    const int32_t want_lowering = opts ? opts->lowering : SCCL_LOWER_AUTO;
+    if (build_staged_tables(*plan, &sg) && sg.n_tasks > 0 && sg.n_levels < STAGED_MAX_LEVELS && plan->vecs_per_chunk > 0) {
+        const int64_t table_bytes = (int64_t)sg.table.size() * 4;
+        const int64_t room = STAGED_LDS_LIMIT - table_bytes;                 // bytes left for the cells
+        const int64_t max_slice = room > 0 ? room / ((int64_t)sg.n_cells * W) : 0;   // vectors per cell that fit
+        if (max_slice >= 1) {
+            int32_t sv;
+            if (opts && opts->slice_vectors) {
+                sv = opts->slice_vectors;
+            } else {
+                // Latency bound either way: one vector per cell while at most 64 workgroups result, longer
+                // slices beyond (measured: 16-byte pieces of a 128-byte line shared by many workgroups on
+                // different XCDs cost more than the parallelism gains).
+                sv = pow2_at_least((plan->vecs_per_chunk + 63) / 64);
+                while (sv > 1 && sv > max_slice) sv >>= 1;
+            }
+            if (sv <= max_slice) {
+                sg.available = true;
+                sg.log_slice_vectors = log2_of(sv);
+                sg.num_slices = (plan->vecs_per_chunk + sv - 1) / sv;
+                sg.lds_bytes = (int32_t)(table_bytes + (int64_t)sg.n_cells * sv * W);
+                // one lane per vector of the widest phase (loading, the widest level, storing), up to 1024
+                const int64_t widest = (int64_t)std::max(std::max(sg.n_in, sg.n_out), sg.max_level_tasks) * sv;
+                int32_t th = (opts && opts->staged_threads) ? opts->staged_threads
+                                                            : std::min(1024, std::max(64, pow2_at_least(widest)));
+                sg.threads = th;
+            }
+        }
+    }
+    if (want_lowering == SCCL_LOWER_STAGED && !sg.available) return SCCL_ERR_INVALID_ARG;
+    const bool small = (int64_t)P * st.bytes_per_rank <= STAGED_AUTO_TOTAL_BYTES;
+    plan->lowering = (want_lowering == SCCL_LOWER_STAGED || (want_lowering == SCCL_LOWER_AUTO && sg.available && small))
+                         ? SCCL_LOWER_STAGED : SCCL_LOWER_MEMORY;
+    st.lowering = plan->lowering;
+    st.staged_available = sg.available ? 1 : 0;
+    st.num_cells = sg.n_cells; st.num_cells_loaded = sg.n_in; st.num_cells_stored = sg.n_out;
+    st.num_levels = sg.n_levels; st.max_level_tasks = sg.max_level_tasks;
+    st.slice_vectors = sg.available ? (1 << sg.log_slice_vectors) : 0;
+    st.staged_threads = sg.threads;
+    st.staged_lds_bytes = sg.lds_bytes;
+    st.num_slices = sg.num_slices;
     return SCCL_OK;
 }

@@ -24,6 +24,7 @@ SCCL_I32, SCCL_F32, SCCL_F16 = 0, 1, 2
 DTYPE_CODES = {"i32": SCCL_I32, "f32": SCCL_F32, "f16": SCCL_F16}
 SCCL_COPY, SCCL_REDUCE_SUM = 0, 1
 SCCL_PLAN_HOST_ONLY = 1
+SCCL_LOWER_AUTO, SCCL_LOWER_MEMORY, SCCL_LOWER_STAGED = 0, 1, 2
 
 
 class sccl_edge_t(ctypes.Structure):
@@ -58,7 +59,8 @@ class sccl_schedule_t(ctypes.Structure):
 class sccl_options_t(ctypes.Structure):
     _fields_ = [("flags", ctypes.c_uint32), ("block_threads", ctypes.c_int32),
                 ("vectors_per_thread", ctypes.c_int32), ("max_workgroups", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("lowering", ctypes.c_int32), ("slice_vectors", ctypes.c_int32),
+                ("staged_threads", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class sccl_stats_t(ctypes.Structure):
@@ -70,7 +72,12 @@ class sccl_stats_t(ctypes.Structure):
                 ("bytes_per_rank", ctypes.c_int64), ("bytes_min", ctypes.c_int64),
                 ("bytes_unfused", ctypes.c_int64), ("vector_bytes", ctypes.c_int32),
                 ("block_threads", ctypes.c_int32), ("vectors_per_thread", ctypes.c_int32),
-                ("num_work_items", ctypes.c_int64), ("grid_workgroups", ctypes.c_int32)]
+                ("num_work_items", ctypes.c_int64), ("grid_workgroups", ctypes.c_int32),
+                ("lowering", ctypes.c_int32), ("staged_available", ctypes.c_int32), ("num_cells", ctypes.c_int32),
+                ("num_cells_loaded", ctypes.c_int32), ("num_cells_stored", ctypes.c_int32),
+                ("num_levels", ctypes.c_int32), ("max_level_tasks", ctypes.c_int32),
+                ("slice_vectors", ctypes.c_int32), ("staged_threads", ctypes.c_int32),
+                ("staged_lds_bytes", ctypes.c_int32), ("num_slices", ctypes.c_int64)]
 
     def as_dict(self):
         return {name: getattr(self, name) for name, _ in self._fields_}
@@ -173,7 +180,8 @@ def sccl_plan_create(topology: Topology, collective: Collective, schedule: Sched
                      options: Optional[dict] = None) -> Plan:
     """sccl_plan_create / sccl_plan_create_ex: marshal the three descriptions and return the plan.
 
-    options: dict with any of flags, block_threads, vectors_per_thread, max_workgroups.
+    options: dict with any of the fields of sccl_options_t (flags, block_threads, vectors_per_thread,
+    max_workgroups, lowering, slice_vectors, staged_threads).
     Raises ScclError carrying the library's status on failure.
     """
     L = lib()

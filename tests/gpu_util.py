@@ -23,18 +23,40 @@ def host_inputs(dist, dtype, seed, P, G, epc, pre=None):
 
 
 def run_both(topo, coll, sched, dtype, bufs, epc, options=None, label="", mode="sccl_execute", slot=None, slots_per_rank=0):
-    """Oracle on copies of `bufs`, library on device copies; returns (oracle buffers, gpu buffers as numpy)."""
+    """Oracle on copies of `bufs`, library on device copies; returns (oracle buffers, gpu buffers as numpy).
+
+    sccl_execute has two lowerings (through memory, staged in the local data share).  Unless `options` names
+    one, the case runs under BOTH -- the staged one whenever the plan says it is available -- each is compared
+    with the oracle here, and the through-memory result is returned."""
     import torch
-    print(f"[case] {label} {mode} P={coll.num_nodes} G={coll.num_chunks} epc={epc} dtype={dtype} opts={options}", flush=True)
     want = [b.copy() for b in bufs]
     ex.execute(dtype, coll.num_chunks, epc, sched, want, slot=slot, slots_per_rank=slots_per_rank)
-    dev = [torch.from_numpy(b.copy()).cuda() for b in bufs]
-    plan = sccl.sccl_plan_create(*to_binding(topo, coll, sched, dtype, epc, slot, slots_per_rank), options=options)
-    getattr(sccl, mode)(plan, dev)
-    torch.cuda.synchronize()
-    got = [d.cpu().numpy() for d in dev]
-    sccl.sccl_plan_destroy(plan)
-    return want, got
+    args = to_binding(topo, coll, sched, dtype, epc, slot, slots_per_rank)
+    explicit = mode != "sccl_execute" or (options is not None and options.get("lowering", 0) != 0)
+    lowerings = [None] if explicit else [sccl.SCCL_LOWER_MEMORY, sccl.SCCL_LOWER_STAGED]
+    result = None
+    for low in lowerings:
+        opts = dict(options or {})
+        if low is not None:
+            opts["lowering"] = low
+        print(f"[case] {label} {mode} P={coll.num_nodes} G={coll.num_chunks} epc={epc} dtype={dtype} opts={opts}", flush=True)
+        try:
+            plan = sccl.sccl_plan_create(*args, options=opts or None)
+        except sccl.ScclError as e:
+            if low == sccl.SCCL_LOWER_STAGED and e.name == "SCCL_ERR_INVALID_ARG":
+                print("[case]   staged lowering not available for this plan", flush=True)
+                continue
+            raise
+        dev = [torch.from_numpy(b.copy()).cuda() for b in bufs]
+        getattr(sccl, mode)(plan, dev)
+        torch.cuda.synchronize()
+        got = [d.cpu().numpy() for d in dev]
+        sccl.sccl_plan_destroy(plan)
+        if result is None:
+            result = got
+        else:
+            assert_same_bits(want, got)
+    return want, result
 
 
 def assert_same_bits(want, got):

@@ -40,7 +40,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(sccl.sccl_collective_t) == 56
     assert ctypes.sizeof(sccl.sccl_send_t) == 20
     assert ctypes.sizeof(sccl.sccl_schedule_t) == 32
-    assert ctypes.sizeof(sccl.sccl_options_t) == 20
+    assert ctypes.sizeof(sccl.sccl_options_t) == 32
 
 
 GOOD = [
@@ -242,3 +242,84 @@ def test_slot_maps_are_validated():
     bad = slot.copy(); bad[held[0], 0] = per_rank
     assert plan_status(topo, coll, s, "f32", 8, slot=bad, slots_per_rank=per_rank)[0] == "SCCL_ERR_INVALID_ARG"
     assert plan_status(topo, coll, s, "f32", 8, slot=slot, slots_per_rank=0)[0] == "SCCL_ERR_INVALID_ARG"
+
+
+# ---- the staged lowering: dependency levels and cells are host logic, checked here without a GPU
+
+def _levels_by_hand(sched):
+    """Longest chain of dependent groups, from the definition: a group depends on an earlier group if it reads a
+    cell that group wrote, or writes a cell that group read or wrote."""
+    from collections import OrderedDict
+    groups = []
+    for s in range(sched.num_steps):
+        gs = OrderedDict()
+        for (c, n, m, st, op) in sched.sends.tolist():
+            if st != s:
+                continue
+            if op == COPY:
+                gs.setdefault((0, c, n), []).append(m)
+            else:
+                gs.setdefault((1, c, m), []).append(n)
+        for (kind, c, a), others in gs.items():
+            reads = {(c, a)} | ({(c, o) for o in others} if kind == 1 else set())
+            writes = {(c, a)} if kind == 1 else {(c, o) for o in others}
+            groups.append((reads, writes))
+    depth = []
+    for i, (r, w) in enumerate(groups):
+        d = 1
+        for j in range(i):
+            rj, wj = groups[j]
+            if (r & wj) or (w & rj) or (w & wj):
+                d = max(d, depth[j] + 1)
+        depth.append(d)
+    cells = set().union(*[r | w for r, w in groups])
+    written = set().union(*[w for _, w in groups])
+    first_read = set()
+    seen = set()
+    for r, w in groups:
+        first_read |= (r - seen)
+        seen |= r | w
+    return max(depth), len(cells), len(first_read), len(written)
+
+
+@pytest.mark.parametrize("topo,C,kind", GOOD)
+def test_staged_tables_follow_the_dependency_structure(topo, C, kind):
+    P = topo.num_nodes
+    ag = col.allgather(P, C)
+    s = gen.ring_allgather(P, C) if kind == "ring" else gen.greedy_bfs(topo, ag)
+    ar, arc = gen.compose_allreduce(s, ag)
+    for coll, sched in ((ag, s), (arc, ar)):
+        name, st = plan_status(topo, coll, sched, "f32", 4)
+        assert name == "SCCL_OK" and st["staged_available"] == 1
+        levels, cells, loaded, stored = _levels_by_hand(sched)
+        assert (st["num_levels"], st["num_cells"], st["num_cells_loaded"], st["num_cells_stored"]) == (levels, cells, loaded, stored)
+        assert st["num_levels"] <= sched.num_steps
+        assert st["lowering"] == sccl.SCCL_LOWER_STAGED           # 16 bytes per chunk: small
+
+
+def test_staged_lowering_choice_and_limits():
+    topo, ag = tp.torus2d(4, 4), col.allgather(16, 4)
+    s = gen.greedy_bfs(topo, ag)
+    ar, arc = gen.compose_allreduce(s, ag)
+    # torus Allgather: every chunk reaches 15 ranks over a tree of depth <= diameter + waiting; Allreduce twice that
+    _, st = plan_status(topo, ag, s, "f32", 4)
+    assert st["num_cells"] == 16 * 64 and st["num_cells_loaded"] == 64 and st["num_cells_stored"] == 15 * 64
+    _, st2 = plan_status(topo, arc, ar, "f32", 4)
+    assert st2["num_cells_loaded"] == 16 * 64 and st2["num_levels"] == 2 * st["num_levels"]
+    # auto: staged up to 512 KiB over all ranks, through memory above
+    for epc, want in ((1 << 7, sccl.SCCL_LOWER_STAGED), (1 << 8, sccl.SCCL_LOWER_MEMORY)):
+        _, st = plan_status(topo, arc, ar, "f32", epc)
+        assert P_bytes(st) == 16 * 64 * epc * 4 and st["lowering"] == want
+    # explicit choices
+    assert plan_status(topo, arc, ar, "f32", 1 << 14, options={"lowering": sccl.SCCL_LOWER_STAGED})[1]["lowering"] == sccl.SCCL_LOWER_STAGED
+    assert plan_status(topo, arc, ar, "f32", 4, options={"lowering": sccl.SCCL_LOWER_MEMORY})[1]["lowering"] == sccl.SCCL_LOWER_MEMORY
+    # a slice of every cell must fit 160 KiB together with the tables: 1024 cells x 16 vectors x 16 B is too much
+    assert plan_status(topo, arc, ar, "f32", 1 << 10, options={"lowering": sccl.SCCL_LOWER_STAGED, "slice_vectors": 16})[0] == "SCCL_ERR_INVALID_ARG"
+    _, st = plan_status(topo, arc, ar, "f32", 1 << 10, options={"lowering": sccl.SCCL_LOWER_STAGED, "slice_vectors": 4})
+    assert st["slice_vectors"] == 4 and st["num_slices"] == 64 and st["staged_lds_bytes"] <= 160 * 1024
+    for bad in ({"lowering": 3}, {"slice_vectors": 3}, {"staged_threads": 96}, {"reserved": 1}):
+        assert plan_status(topo, arc, ar, "f32", 4, options=bad)[0] == "SCCL_ERR_INVALID_ARG"
+
+
+def P_bytes(st):
+    return st["num_nodes"] * st["bytes_per_rank"]
