@@ -274,6 +274,35 @@ def main():
                 f.write(f"| {r[0]} | {r[1]} | {r[2]} | {r[3]} | {r[4]} | {r[5]} | {r[6]:.1f} | {r[7]:.1f} | {r[8]:.1f} | "
                         f"{100 * r[8] / HBM_PEAK_GBS:.1f} | {r[9]} | {r[10]} | {r[11]} | {fmt(r[12])} | {fmt(r[13])} | "
                         f"{fmt(r[14])} | {fmt(r[15])} |\n")
+        # ---- the paper's size-dependent choice between two algorithms (section 5.5) on this hardware: the
+        # latency-optimal and the bandwidth-optimal torus algorithm at every size, the (alpha, beta) of the cost
+        # model fitted to the measurements, and what the model would have chosen.
+        with open(args.report, "a") as f:
+            f.write("\n| collective | bytes/rank | latency-optimal: us | bandwidth-optimal: us | measured best | model's choice "
+                    "| model us (latency / bandwidth) |\n|---|---|---|---|---|---|---|\n")
+            for coll in ("allgather", "allreduce"):
+                meas = []
+                for size in workloads.sweep_sizes():
+                    pair = []
+                    for alg in ("latency", "bandwidth"):
+                        w = workloads.sweep_workload(coll, size, alg)
+                        steps = 5 if size >= (1 << 30) else 20
+                        med, _, st_ = median_us(w, steps, "sccl_execute")
+                        # the model's two coordinates: a = S, b = (R / C) * L = R * chunk bytes
+                        pair.append((med * 1e-6, float(st_["num_steps"]), float(st_["num_rounds"]) * st_["chunk_bytes"]))
+                    meas.append((size, pair))
+                a = [p[1] for _, pair in meas for p in pair]
+                b = [p[2] for _, pair in meas for p in pair]
+                t = [p[0] for _, pair in meas for p in pair]
+                alpha, beta = sccl.sccl_cost_fit(a, b, t)
+                for size, pair in meas:
+                    model = [p[1] * alpha + p[2] * beta for p in pair]
+                    f.write(f"| {coll} | {size} | {pair[0][0] * 1e6:.1f} | {pair[1][0] * 1e6:.1f} | "
+                            f"{'latency' if pair[0][0] <= pair[1][0] else 'bandwidth'} | "
+                            f"{'latency' if model[0] <= model[1] else 'bandwidth'} | {model[0] * 1e6:.1f} / {model[1] * 1e6:.1f} |\n")
+                f.write(f"\n{coll}: fitted alpha = {alpha * 1e6:.3f} us per step, beta = {beta * 1e12:.4f} ps per byte "
+                        f"(1 / beta = {1e-9 / beta if beta > 0 else float('inf'):.0f} GB/s per link-equivalent)\n")
+                print(f"[report] {coll}: alpha {alpha * 1e6:.3f} us, beta {beta * 1e12:.4f} ps/B", file=sys.stderr, flush=True)
     print(json.dumps(line), flush=True)
 
 

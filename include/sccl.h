@@ -164,6 +164,7 @@ typedef struct {
     int64_t num_copy_groups;       /* (step, chunk, src) groups */
     int64_t num_reduce_groups;     /* (step, chunk, dst) groups */
     int32_t max_fan_in, max_fan_out;
+    int32_t chunks_per_node;       /* C: the most chunks any node holds in pre (section 3.2.2) */
     int64_t chunk_bytes;
     int64_t bytes_per_rank;        /* G (or slots_per_rank) * chunk_bytes */
     int64_t bytes_min;             /* sum over copy groups of (1 + k) chunks and over reduce groups of (k + 2) chunks */
@@ -239,6 +240,29 @@ sccl_status_t sccl_plan_stats(const sccl_plan_t* plan, sccl_stats_t* out_stats);
 void sccl_plan_destroy(sccl_plan_t* plan);
 
 const char* sccl_status_string(sccl_status_t status);
+
+/*
+ * The paper's cost model (section 3.6): with a node's L input bytes cut into C chunks, step s of r_s rounds
+ * takes alpha + (r_s / C) * L * beta seconds, the plan S * alpha + (R / C) * L * beta.  Here L = C *
+ * chunk_bytes of the plan.  alpha (seconds per step) and beta (seconds per byte) must be >= 0.  Host only.
+ */
+sccl_status_t sccl_plan_cost(const sccl_plan_t* plan, double alpha, double beta, double* out_seconds);
+
+/*
+ * Which of several plans for the same collective and input size the cost model prefers (section 5.5: the
+ * latency-optimal algorithm for small inputs, the bandwidth-optimal one for large inputs): the index of the
+ * plan with the lowest sccl_plan_cost, the earliest on ties.  plans is a host array of num_plans >= 1 plans.
+ */
+sccl_status_t sccl_select_plan(const sccl_plan_t* const* plans, int32_t num_plans, double alpha, double beta,
+                               int32_t* out_best);
+
+/*
+ * Fit of the model's two constants to n >= 2 measurements t[i] of algorithms with latency cost a[i] (= S) and
+ * bandwidth cost b[i] (= R / C * L, in bytes): least squares for t = a * alpha + b * beta.  Host arrays.
+ * SCCL_ERR_INVALID_ARG if the samples do not determine both constants (a and b proportional).
+ */
+sccl_status_t sccl_cost_fit(int32_t n, const double* a, const double* b, const double* t, double* out_alpha,
+                            double* out_beta);
 
 /*
  * Measurement aid, not part of the method: a plain 16-byte-per-lane copy

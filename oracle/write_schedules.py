@@ -83,6 +83,14 @@ def configurations():
     out["cfg5_allgather_torus4x4"] = (t, ag, s)
     ar, arc = gen.compose_allreduce(s, ag)
     out["cfg5_allreduce_torus4x4"] = (t, arc, ar)
+    #    and the latency-optimal algorithm for the same topology, from the exact search: one chunk per node,
+    #    (C, S, R) = (1, 4, 4) with S the diameter; Allreduce (16, 8, 8).  The pair the cost model chooses between.
+    from . import synthesize as syn
+    ag = col.allgather(16, 1)
+    s = syn.solve_instance(t, ag, 4, 4)
+    out["cfg5_allgather_torus4x4_latency"] = (t, ag, s)
+    ar, arc = gen.compose_allreduce(s, ag)
+    out["cfg5_allreduce_torus4x4_latency"] = (t, arc, ar)
     return out
 
 

@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libsccl.so")
-SOURCES = [os.path.join(HERE, "csrc", "plan.cpp"), os.path.join(HERE, "csrc", "exec.hip")]
+SOURCES = [os.path.join(HERE, "csrc", "plan.cpp"), os.path.join(HERE, "csrc", "cost.cpp"),
+           os.path.join(HERE, "csrc", "exec.hip")]
 DEPS = SOURCES + [os.path.join(HERE, "csrc", "plan.hpp"), os.path.join(ROOT, "include", "sccl.h")]
 
 

@@ -1,0 +1,51 @@
+// The paper's (alpha, beta) cost model on the library side (section 3.6) and what it is used for there
+// (section 5.5): choosing, per input size, among several algorithms for the same collective.  Host only.
+#include <cmath>
+
+#include "plan.hpp"
+
+extern "C" {
+
+// S * alpha + (R / C) * L * beta with L = C * chunk_bytes the input bytes of a node.
+sccl_status_t sccl_plan_cost(const sccl_plan_t* plan, double alpha, double beta, double* out_seconds) {
+    if (!plan || !out_seconds || !(alpha >= 0.0) || !(beta >= 0.0)) return SCCL_ERR_INVALID_ARG;
+    const sccl_stats_t& st = plan->stats;
+    const double L = (double)st.chunks_per_node * (double)st.chunk_bytes;
+    double t = 0.0;
+    for (int32_t r : plan->rounds) t += alpha + ((double)r / (double)st.chunks_per_node) * L * beta;   // per step
+    *out_seconds = t;
+    return SCCL_OK;
+}
+
+sccl_status_t sccl_select_plan(const sccl_plan_t* const* plans, int32_t num_plans, double alpha, double beta,
+                               int32_t* out_best) {
+    if (!plans || num_plans < 1 || !out_best) return SCCL_ERR_INVALID_ARG;
+    int32_t best = -1;
+    double best_t = 0.0;
+    for (int32_t i = 0; i < num_plans; i++) {
+        double t;
+        const sccl_status_t st = sccl_plan_cost(plans[i], alpha, beta, &t);
+        if (st != SCCL_OK) return st;
+        if (best < 0 || t < best_t) { best = i; best_t = t; }     // ties go to the earlier plan
+    }
+    *out_best = best;
+    return SCCL_OK;
+}
+
+// Least squares for t_i = a_i * alpha + b_i * beta (no intercept): the normal equations of a 2-column system.
+sccl_status_t sccl_cost_fit(int32_t n, const double* a, const double* b, const double* t, double* out_alpha,
+                            double* out_beta) {
+    if (n < 2 || !a || !b || !t || !out_alpha || !out_beta) return SCCL_ERR_INVALID_ARG;
+    double saa = 0, sab = 0, sbb = 0, sat = 0, sbt = 0;
+    for (int32_t i = 0; i < n; i++) {
+        saa += a[i] * a[i]; sab += a[i] * b[i]; sbb += b[i] * b[i];
+        sat += a[i] * t[i]; sbt += b[i] * t[i];
+    }
+    const double det = saa * sbb - sab * sab;
+    if (!(std::fabs(det) > 1e-300 * (saa * sbb + 1e-300)) || !std::isfinite(det)) return SCCL_ERR_INVALID_ARG;   // collinear samples
+    *out_alpha = (sat * sbb - sbt * sab) / det;
+    *out_beta = (saa * sbt - sab * sat) / det;
+    return SCCL_OK;
+}
+
+}  // extern "C"

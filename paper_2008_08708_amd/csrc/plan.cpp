@@ -374,6 +374,13 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
     st.num_sends = N;
     st.num_copy_groups = n_copy_groups; st.num_reduce_groups = n_reduce_groups;
     st.max_fan_in = max_in; st.max_fan_out = max_out;
+    st.chunks_per_node = 0;
+    for (int32_t n = 0; n < P; n++) {
+        int32_t have = 0;
+        for (int32_t c = 0; c < G; c++) have += coll->pre[(size_t)c * P + n] != 0;
+        st.chunks_per_node = std::max(st.chunks_per_node, have);
+    }
+    if (st.chunks_per_node == 0) st.chunks_per_node = 1;
     st.chunk_bytes = chunk_bytes;
     st.bytes_per_rank = chunk_bytes * slots;
     st.bytes_min = chunks_min * chunk_bytes;

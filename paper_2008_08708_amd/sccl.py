@@ -68,7 +68,7 @@ class sccl_stats_t(ctypes.Structure):
                 ("num_steps", ctypes.c_int32), ("num_rounds", ctypes.c_int32), ("k", ctypes.c_int32),
                 ("num_sends", ctypes.c_int64), ("num_copy_groups", ctypes.c_int64),
                 ("num_reduce_groups", ctypes.c_int64), ("max_fan_in", ctypes.c_int32),
-                ("max_fan_out", ctypes.c_int32), ("chunk_bytes", ctypes.c_int64),
+                ("max_fan_out", ctypes.c_int32), ("chunks_per_node", ctypes.c_int32), ("chunk_bytes", ctypes.c_int64),
                 ("bytes_per_rank", ctypes.c_int64), ("bytes_min", ctypes.c_int64),
                 ("bytes_unfused", ctypes.c_int64), ("vector_bytes", ctypes.c_int32),
                 ("block_threads", ctypes.c_int32), ("vectors_per_thread", ctypes.c_int32),
@@ -85,7 +85,7 @@ class sccl_stats_t(ctypes.Structure):
 
 EXPORTS = ["sccl_plan_create", "sccl_plan_create_ex", "sccl_execute", "sccl_execute_stepwise", "sccl_execute_memcpy",
            "sccl_plan_stats", "sccl_plan_destroy",
-           "sccl_status_string", "sccl_copy_kernel"]
+           "sccl_status_string", "sccl_copy_kernel", "sccl_plan_cost", "sccl_select_plan", "sccl_cost_fit"]
 
 _lib = None
 
@@ -122,6 +122,14 @@ def lib() -> ctypes.CDLL:
         L.sccl_status_string.argtypes = [ctypes.c_int]
         L.sccl_copy_kernel.restype = ctypes.c_int
         L.sccl_copy_kernel.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.sccl_plan_cost.restype = ctypes.c_int
+        L.sccl_plan_cost.argtypes = [ctypes.c_void_p, ctypes.c_double, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
+        L.sccl_select_plan.restype = ctypes.c_int
+        L.sccl_select_plan.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32, ctypes.c_double, ctypes.c_double,
+                                       ctypes.POINTER(ctypes.c_int32)]
+        L.sccl_cost_fit.restype = ctypes.c_int
+        L.sccl_cost_fit.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                    ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         _lib = L
     return _lib
 
@@ -278,3 +286,34 @@ def sccl_copy_kernel(dst, src, nbytes: int, stream=None) -> None:
                                 ctypes.c_size_t(int(nbytes)), ctypes.c_void_p(int(stream)))
     if st != SCCL_OK:
         raise ScclError(st, "sccl_copy_kernel")
+
+
+def sccl_plan_cost(plan: Plan, alpha: float, beta: float) -> float:
+    """Seconds the paper's (alpha, beta) model gives the plan."""
+    out = ctypes.c_double()
+    st = lib().sccl_plan_cost(plan.handle, float(alpha), float(beta), ctypes.byref(out))
+    if st != SCCL_OK:
+        raise ScclError(st, "sccl_plan_cost")
+    return out.value
+
+
+def sccl_select_plan(plans: Sequence[Plan], alpha: float, beta: float) -> int:
+    """Index of the plan the cost model prefers."""
+    arr = (ctypes.c_void_p * max(1, len(plans)))(*[p.handle for p in plans])
+    out = ctypes.c_int32()
+    st = lib().sccl_select_plan(arr, len(plans), float(alpha), float(beta), ctypes.byref(out))
+    if st != SCCL_OK:
+        raise ScclError(st, "sccl_select_plan")
+    return out.value
+
+
+def sccl_cost_fit(a: Sequence[float], b: Sequence[float], t: Sequence[float]) -> Tuple[float, float]:
+    """(alpha, beta) of the least-squares fit t = a * alpha + b * beta."""
+    aa, bb, tt = (np.ascontiguousarray(x, dtype=np.float64) for x in (a, b, t))
+    if not (aa.shape == bb.shape == tt.shape and aa.ndim == 1):
+        raise ValueError("a, b, t must be 1-d arrays of one length")
+    al, be = ctypes.c_double(), ctypes.c_double()
+    st = lib().sccl_cost_fit(aa.size, aa.ctypes.data, bb.ctypes.data, tt.ctypes.data, ctypes.byref(al), ctypes.byref(be))
+    if st != SCCL_OK:
+        raise ScclError(st, "sccl_cost_fit")
+    return al.value, be.value

@@ -43,7 +43,10 @@ def sweep_sizes() -> List[int]:
     return [1024 * 4 ** i for i in range(11)]
 
 
-def sweep_workload(collective: str, bytes_per_rank: int) -> Workload:
-    assert collective in ("allgather", "allreduce")
-    return Workload(f"cfg5_{collective}_{bytes_per_rank}", f"cfg5_{collective}_torus4x4", "f32", "uniform", 5,
+def sweep_workload(collective: str, bytes_per_rank: int, algorithm: str = "bandwidth") -> Workload:
+    """Config 5 at one size.  algorithm: "bandwidth" = the greedy schedule with four chunks per node, (4,15,15),
+    bandwidth-optimal on the torus; "latency" = the exact search's (1,4,4), as many steps as the diameter."""
+    assert collective in ("allgather", "allreduce") and algorithm in ("bandwidth", "latency")
+    suffix = "" if algorithm == "bandwidth" else "_latency"
+    return Workload(f"cfg5_{collective}_{bytes_per_rank}{suffix}", f"cfg5_{collective}_torus4x4{suffix}", "f32", "uniform", 5,
                     bytes_per_rank, collective == "allgather")

@@ -22,6 +22,8 @@ CASES = [("cfg2", workloads.WORKLOADS["cfg2"]), ("cfg3", workloads.WORKLOADS["cf
 for coll in ("allgather", "allreduce"):
     for size in (1 << 10, 1 << 16, 1 << 22, 1 << 28, 1 << 30):
         CASES.append((f"cfg5-{coll}-{size}", workloads.sweep_workload(coll, size)))
+    for size in (1 << 10, 1 << 20, 1 << 28):               # the latency-optimal algorithm the selection is measured with
+        CASES.append((f"cfg5-{coll}-latency-{size}", workloads.sweep_workload(coll, size, "latency")))
 
 
 def windows(epc, tile_elems, n=1536):

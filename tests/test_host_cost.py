@@ -1,0 +1,120 @@
+"""CPU tests of the library's cost model, plan selection and fit (host only) against the oracle's cost.py, the
+running times the paper prints, and closed forms."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from conftest import read_examples, read_table
+from helpers import to_binding
+from oracle import collective as col
+from oracle import cost
+from oracle import generate as gen
+from oracle import topology as tp
+from paper_2008_08708_amd import sccl
+
+HOST = {"flags": sccl.SCCL_PLAN_HOST_ONLY}
+
+
+def host_plan(topo, coll, sched, dtype="f32", epc=1024):
+    return sccl.sccl_plan_create(*to_binding(topo, coll, sched, dtype, epc), options=HOST)
+
+
+def test_chunks_per_node_is_the_papers_C():
+    for topo, C in ((tp.ring(8), 2), (tp.hcm8(), 1), (tp.torus2d(4, 4), 4)):
+        P = topo.num_nodes
+        ag = col.allgather(P, C)
+        s = gen.ring_allgather(P, C) if topo.name.startswith("ring") else gen.greedy_bfs(topo, ag)
+        ar, arc = gen.compose_allreduce(s, ag)
+        p1, p2 = host_plan(topo, ag, s), host_plan(topo, arc, ar)
+        assert sccl.sccl_plan_stats(p1)["chunks_per_node"] == C            # Allgather: G = P * C
+        assert sccl.sccl_plan_stats(p2)["chunks_per_node"] == P * C        # Allreduce rows of Tables 4 and 5: C = P * C_allgather
+
+
+def test_cost_equals_the_oracles_running_time():
+    alpha, beta = 3.5e-6, 1.0 / 25e9
+    for topo, C, kind in ((tp.ring(8), 2, "ring"), (tp.dgx1(), 2, "greedy"), (tp.torus2d(4, 4), 4, "greedy")):
+        P = topo.num_nodes
+        ag = col.allgather(P, C)
+        s = gen.ring_allgather(P, C) if kind == "ring" else gen.greedy_bfs(topo, ag)
+        ar, arc = gen.compose_allreduce(s, ag)
+        for coll, sched, Cn in ((ag, s, C), (arc, ar, P * C)):
+            for epc in (1, 1000, 1 << 20):
+                L = Cn * epc * 4
+                got = sccl.sccl_plan_cost(host_plan(topo, coll, sched, "f32", epc), alpha, beta)
+                want = cost.running_time(Cn, sched.rounds, L, alpha, beta)
+                assert got == pytest.approx(want, rel=1e-12)
+                a, b = cost.cost_pair(Cn, sched.num_steps, sched.num_rounds)
+                assert got == pytest.approx(a * alpha + float(b) * L * beta, rel=1e-12)
+
+
+def test_ring_allgather_costs_what_the_paper_prints_for_its_ring_example():
+    # the 8-ring row (2,7,7) of
+    # Table 5: 7 alpha + 7/2 L beta
+    rows = {(r[0], r[1], r[2], r[3]): (r[4], r[5]) for r in read_table("table5_z52.txt")}
+    a, b = rows[("allgather", 2, 7, 7)]
+    topo, ag = tp.ring(8), col.allgather(8, 2)
+    p = host_plan(topo, ag, gen.ring_allgather(8, 2), "f32", 1 << 18)
+    L = 2 * (1 << 18) * 4
+    assert sccl.sccl_plan_cost(p, 1.0, 0.0) == pytest.approx(a)
+    assert sccl.sccl_plan_cost(p, 0.0, 1.0) == pytest.approx(float(b) * L)
+
+
+def test_selection_switches_at_the_closed_form_crossover():
+    # the paper's two DGX-1 Allgathers (section 2.4, 2.5): 2 alpha + 3/2 L beta and 3 alpha + 7/6 L beta tie at
+    # L* = alpha / ((3/2 - 7/6) beta) = 3 alpha / beta.  Built here as two rings' worth of (C, S, R) by hand:
+    # any two plans with those cost pairs do, since the model sees only (S, R, C, L).
+    ex = read_examples()
+    lat = (int(ex["synth_dgx1_lat_optimal_cost"][0]), Fraction(ex["synth_dgx1_lat_optimal_cost"][1]))
+    bw = (int(ex["synth_dgx1_bw_optimal_cost"][0]), Fraction(ex["synth_dgx1_bw_optimal_cost"][1]))
+    from oracle import synthesize as syn
+    topo = tp.dgx1()
+    ag2, ag6 = col.allgather(8, 2), col.allgather(8, 6)
+    s_lat = syn.solve_instance(topo, ag2, 2, 3)
+    s_bw = gen.greedy_bfs(topo, ag6)                      # any valid 6-chunk schedule: its own (S, R) is used below
+    assert cost.cost_pair(2, s_lat.num_steps, s_lat.num_rounds) == lat
+    alpha, beta = 2e-6, 1e-10
+    for L in (1200, 12_000, 120_000, 1_200_000, 12_000_000):       # divisible by 2*4 and 6*4
+        p_lat = host_plan(topo, ag2, s_lat, "f32", L // (2 * 4))
+        p_bw = host_plan(topo, ag6, s_bw, "f32", L // (6 * 4))
+        t_lat, t_bw = sccl.sccl_plan_cost(p_lat, alpha, beta), sccl.sccl_plan_cost(p_bw, alpha, beta)
+        assert t_lat == pytest.approx(lat[0] * alpha + float(lat[1]) * L * beta)
+        a_bw, b_bw = cost.cost_pair(6, s_bw.num_steps, s_bw.num_rounds)
+        assert t_bw == pytest.approx(a_bw * alpha + float(b_bw) * L * beta)
+        best = sccl.sccl_select_plan([p_lat, p_bw], alpha, beta)
+        assert best == (0 if t_lat <= t_bw else 1)
+        if b_bw < lat[1] and a_bw > lat[0]:               # a real trade-off: closed-form crossover
+            L_star = (a_bw - lat[0]) * alpha / (float(lat[1] - b_bw) * beta)
+            assert best == (0 if L <= L_star else 1)
+    # the paper's own pair: crossover 3 alpha / beta
+    assert (bw[0] - lat[0]) / float(lat[1] - bw[1]) == pytest.approx(3.0)
+
+
+def test_selection_ties_and_errors():
+    topo, ag = tp.ring(4), col.allgather(4, 1)
+    p = host_plan(topo, ag, gen.greedy_bfs(topo, ag))
+    assert sccl.sccl_select_plan([p, p, p], 1e-6, 1e-9) == 0
+    with pytest.raises(sccl.ScclError):
+        sccl.sccl_select_plan([], 1e-6, 1e-9)
+    with pytest.raises(sccl.ScclError):
+        sccl.sccl_plan_cost(p, -1.0, 0.0)
+    with pytest.raises(sccl.ScclError):
+        sccl.sccl_plan_cost(p, float("nan"), 0.0)
+
+
+def test_fit_recovers_the_constants_and_matches_numpy():
+    rng = np.random.default_rng(7)
+    alpha, beta = 4.2e-6, 1.0 / 33e9
+    a = rng.integers(2, 15, size=40).astype(np.float64)
+    b = rng.uniform(1e3, 1e9, size=40)
+    t = a * alpha + b * beta
+    al, be = sccl.sccl_cost_fit(a, b, t)
+    assert al == pytest.approx(alpha, rel=1e-9) and be == pytest.approx(beta, rel=1e-9)
+    noisy = t * (1 + 0.05 * rng.standard_normal(40))
+    al, be = sccl.sccl_cost_fit(a, b, noisy)
+    ref = np.linalg.lstsq(np.stack([a, b], axis=1), noisy, rcond=None)[0]
+    assert al == pytest.approx(ref[0], rel=1e-6) and be == pytest.approx(ref[1], rel=1e-6)
+    with pytest.raises(sccl.ScclError):                    # proportional columns determine nothing
+        sccl.sccl_cost_fit([1.0, 2.0, 3.0], [2.0, 4.0, 6.0], [1.0, 2.0, 3.0])
+    with pytest.raises(sccl.ScclError):
+        sccl.sccl_cost_fit([1.0], [2.0], [1.0])
