@@ -153,6 +153,30 @@ def cpu_baseline(run, wl):
                       f"OpenMP over the element range"}, same
 
 
+def sweep(wl, steps, warmup):
+    """Every launch shape of the through-memory kernel (workgroup size x vectors per lane x workgroups per CU) and,
+    where the cells fit, of the staged kernel (slice x workgroup size); one JSON line each, the best last."""
+    from paper_2008_08708_amd import sccl
+    shapes = [{"lowering": 1, "block_threads": bt, "vectors_per_thread": vt, "max_workgroups": 256 * k}
+              for bt in (64, 128, 256) for vt in (1, 2, 4, 8) for k in (1, 2, 4)]
+    shapes += [{"lowering": 2, "slice_vectors": sv, "staged_threads": th}
+               for sv in (1, 2, 4, 8, 16, 32, 64, 128) for th in (256, 512, 1024)]
+    best = None
+    for o in shapes:
+        try:
+            r = time_workload(wl, steps, warmup, o)
+        except sccl.ScclError:
+            continue                                   # a staged shape whose cells do not fit
+        ms = sorted(r["ms"])
+        st = r["stats"]
+        rec = {"workload": wl.name, "options": o, "grid": st["grid_workgroups"], "median_us": round(ms[len(ms) // 2] * 1e3, 2),
+               "min_us": round(ms[0] * 1e3, 2), "effective_GBs": round(st["bytes_min"] / ms[len(ms) // 2] / 1e6, 1)}
+        print(json.dumps(rec), flush=True)
+        if best is None or rec["median_us"] < best["median_us"]:
+            best = rec
+    print(json.dumps({"best": best}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -165,6 +189,9 @@ def main():
     ap.add_argument("--lowering", type=int, default=0, help="0 = the plan chooses, 1 = through memory, 2 = staged in the local data share")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", default="", metavar="FILE", help="also time the other configurations; markdown table to FILE")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: time --workload under every launch shape of both kernels "
+                         "(the paper's search over thread-block count and size, section 4) and print one JSON line each")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build executes P virtual ranks on ONE GPU; --gpus N with N > 1 is not supported "
@@ -185,6 +212,9 @@ def main():
         wl = workloads.sweep_workload(coll_name, int(size))
     else:
         wl = workloads.WORKLOADS[args.workload]
+    if args.sweep:
+        sweep(wl, args.steps, args.warmup)
+        return
     run = time_workload(wl, args.steps, args.warmup, options or None, keep=True)
     st = run["stats"]
     ms = run["ms"]
