@@ -92,6 +92,34 @@ def time_workload(wl, steps, warmup, options=None, keep=False, mode="sccl_execut
     return out
 
 
+def graph_us_per_execute(wl, count=20, reps=10, options=None):
+    """Microseconds per sccl_execute when `count` of them run back to back inside one HIP graph (values are not
+    restored in between: only the time is of interest).  This is what a launch-bound caller pays per collective."""
+    import torch
+    from paper_2008_08708_amd import schedule_file, sccl
+    sf = schedule_file.load(wl.schedule)
+    work, epc = make_inputs(wl, sf, torch.device("cuda:0"))
+    plan = sccl.sccl_plan_create(*sf.descriptions(wl.dtype, epc), options=options)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(count):
+            sccl.sccl_execute(plan, work, side)
+    times = []
+    for _ in range(reps + 2):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        graph.replay()
+        b.record()
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(b) * 1e3 / count)
+    del graph
+    sccl.sccl_plan_destroy(plan)
+    times = sorted(times[2:])
+    return times[len(times) // 2]
+
+
 def copy_ceiling(nbytes, reps=10):
     """GB/s (read + write) of a plain 16-byte-per-lane copy kernel over nbytes."""
     import torch
@@ -285,25 +313,28 @@ def main():
                     stg_med = median_us(w, steps, "sccl_execute", {"lowering": SCCL_LOWER_STAGED})[0]
                 except ScclError:
                     stg_med = None
+            graph_us = graph_us_per_execute(w) if w.bytes_per_rank <= (1 << 20) else None
             step_med, _, _ = median_us(w, steps, "sccl_execute_stepwise")
             cpy_med = median_us(w, steps, "sccl_execute_memcpy")[0] if s["num_reduce_groups"] == 0 else None
             rows.append((label, s["num_nodes"], w.bytes_per_rank, s["chunk_bytes"], s["num_steps"], s["bytes_min"],
                          med, mn, s["bytes_min"] / (med * 1e-6) / 1e9, "staged" if s["lowering"] == SCCL_LOWER_STAGED else "memory",
-                         s["num_levels"], s["grid_workgroups"], mem_med, stg_med, step_med, cpy_med))
+                         s["num_levels"], s["grid_workgroups"], mem_med, stg_med, step_med, cpy_med, graph_us))
             fmt = lambda x: "-" if x is None else format(x, ".1f")
             print(f"[report] {label}: default ({rows[-1][9]}) {med:.1f} us ({rows[-1][8]:.1f} GB/s), through memory {fmt(mem_med)} us, "
-                  f"staged {fmt(stg_med)} us, per-step kernels {fmt(step_med)} us, per-send copies {fmt(cpy_med)} us",
+                  f"staged {fmt(stg_med)} us, per-step kernels {fmt(step_med)} us, per-send copies {fmt(cpy_med)} us, "
+                  f"in a graph of 20 {fmt(graph_us)} us each",
                   file=sys.stderr, flush=True)
         os.makedirs(os.path.dirname(os.path.abspath(args.report)), exist_ok=True)
         with open(args.report, "w") as f:
             f.write("| workload | P | bytes/rank | chunk bytes | S | bytes_min | sccl_execute: median us | min us | effective GB/s | % of 8 TB/s "
-                    "| lowering | levels | grid | through memory: us | staged: us | one kernel per step: us | one copy per send: us |\n")
-            f.write("|" + "---|" * 17 + "\n")
+                    "| lowering | levels | grid | through memory: us | staged: us | one kernel per step: us | one copy per send: us "
+                    "| each of 20 in one HIP graph: us |\n")
+            f.write("|" + "---|" * 18 + "\n")
             fmt = lambda x: "-" if x is None else format(x, ".1f")
             for r in rows:
                 f.write(f"| {r[0]} | {r[1]} | {r[2]} | {r[3]} | {r[4]} | {r[5]} | {r[6]:.1f} | {r[7]:.1f} | {r[8]:.1f} | "
                         f"{100 * r[8] / HBM_PEAK_GBS:.1f} | {r[9]} | {r[10]} | {r[11]} | {fmt(r[12])} | {fmt(r[13])} | "
-                        f"{fmt(r[14])} | {fmt(r[15])} |\n")
+                        f"{fmt(r[14])} | {fmt(r[15])} | {fmt(r[16])} |\n")
         # ---- the paper's size-dependent choice between two algorithms (section 5.5) on this hardware: the
         # latency-optimal and the bandwidth-optimal torus algorithm at every size, the (alpha, beta) of the cost
         # model fitted to the measurements, and what the model would have chosen.
