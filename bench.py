@@ -38,16 +38,17 @@ def make_inputs(wl, sf, device):
     import torch
     from paper_2008_08708_amd import inputs
     n_elems = wl.bytes_per_rank // wl.elem_bytes
-    epc = n_elems // sf.num_chunks
+    epc = n_elems // sf.positions_per_rank
     bufs = []
     for n in range(sf.num_nodes):
         b = inputs.torch_rank_buffer(wl.dist, wl.dtype, wl.seed, n, n_elems, device)
         if wl.poison_non_owned:
             view = b.view(torch.int32 if wl.elem_bytes == 4 else torch.int16)
             pat = inputs.POISON_U32 if wl.elem_bytes == 4 else inputs.POISON_U16
-            for c in range(sf.num_chunks):
-                if not sf.pre[c, n]:
-                    view[c * epc:(c + 1) * epc] = pat
+            held = {int(c if sf.slot is None else sf.slot[c, n]) for c in range(sf.num_chunks) if sf.pre[c, n]}
+            for k in range(sf.positions_per_rank):
+                if k not in held:
+                    view[k * epc:(k + 1) * epc] = pat
         bufs.append(b)
     return bufs, epc
 
@@ -287,7 +288,7 @@ def main():
         rows = []
         names = [("cfg1", workloads.WORKLOADS["cfg1"]), ("cfg2", workloads.WORKLOADS["cfg2"]),
                  ("cfg3", workloads.WORKLOADS["cfg3"]), ("cfg4", workloads.WORKLOADS["cfg4"]),
-                 ("cfg4b", workloads.WORKLOADS["cfg4b"])]
+                 ("cfg4b", workloads.WORKLOADS["cfg4b"]), ("alltoall", workloads.WORKLOADS["alltoall"])]
         for coll in ("allgather", "allreduce"):
             for size in workloads.sweep_sizes():
                 names.append((f"cfg5 {coll} {size}", workloads.sweep_workload(coll, size)))

@@ -33,7 +33,7 @@ def _rel_word(rel, G, P):
     return "rows", ["".join(str(int(x)) for x in row) for row in rel]
 
 
-def render(name, topo, coll, sched) -> str:
+def render(name, topo, coll, sched, slot=None, slots_per_rank=0) -> str:
     rep = validate(topo, coll, sched)
     if not rep.ok:
         raise RuntimeError(f"{name}: {rep.verdict} {rep.detail}")
@@ -46,6 +46,9 @@ def render(name, topo, coll, sched) -> str:
         out += rows
     for L, b in topo.bw:
         out.append(f"bw {b} " + " ".join(f"{s}>{d}" for (s, d) in sorted(L)))
+    if slot is not None:
+        out.append(f"slots {int(slots_per_rank)}")
+        out += [" ".join(str(int(x)) for x in row) for row in np.asarray(slot).tolist()]
     out.append("rounds " + " ".join(str(r) for r in sched.rounds))
     out.append(f"sends {sched.sends.shape[0]}")
     out += [" ".join(str(int(x)) for x in row) for row in sched.sends.tolist()]
@@ -94,11 +97,31 @@ def configurations():
     return out
 
 
+def layouts():
+    """name -> (slot map, chunks per rank buffer) for the configurations that do not keep chunk c at position c."""
+    cfg = extra_configurations()
+    t, a2a, s = cfg["alltoall_dgx1"]
+    return {"alltoall_dgx1": col.compact_slots(a2a, s.sends)}
+
+
+def extra_configurations():
+    """Schedules beyond the five configurations: the collective the paper gains most on (section 5.5.3), on its
+    own topology.  Alltoall on the DGX-1 graph, eight chunks per node (one per destination): the row (8, 3, 3)
+    of Table 4, found again by the exact search."""
+    from . import synthesize as syn
+    t = tp.dgx1()
+    a2a = col.alltoall(8, 8)
+    return {"alltoall_dgx1": (t, a2a, syn.solve_instance(t, a2a, 3, 3))}
+
+
 def main():
     os.makedirs(OUT, exist_ok=True)
-    for name, (topo, coll, sched) in configurations().items():
+    every = dict(configurations())
+    every.update(extra_configurations())
+    lay = layouts()
+    for name, (topo, coll, sched) in every.items():
         with open(os.path.join(OUT, name + ".txt"), "w") as f:
-            f.write(render(name, topo, coll, sched))
+            f.write(render(name, topo, coll, sched, *lay.get(name, (None, 0))))
         print(name, coll.name, "P", coll.num_nodes, "G", coll.num_chunks, "S", sched.num_steps, "R", sched.num_rounds,
               "sends", sched.sends.shape[0])
 

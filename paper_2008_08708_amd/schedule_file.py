@@ -15,6 +15,8 @@ Format, one record per line, '#' starts a comment:
     pre  <all | scattered | transpose | root:<n> | rows>      (rows: G lines of P 0/1 digits follow)
     post <...>
     bw <b> <src>><dst> [<src>><dst> ...]                      one (L, b) per line
+    slots <K>                                                 optional layout: G lines of P integers follow, the chunk
+                                                              position of chunk c in rank n's buffer of K chunks, -1 = never held
     rounds <r_0> ... <r_{S-1}>
     sends <count>
     <chunk> <src> <dst> <step> <op>                           count lines, order significant
@@ -23,7 +25,7 @@ from __future__ import annotations
 
 import os
 from dataclasses import dataclass
-from typing import List, Tuple
+from typing import List, Optional, Tuple
 
 import numpy as np
 
@@ -45,11 +47,19 @@ class ScheduleFile:
     bw: List[Tuple[List[Tuple[int, int]], int]]
     rounds: List[int]
     sends: np.ndarray
+    slot: Optional[np.ndarray] = None        # G x P chunk positions, or None: chunk c at position c
+    slots_per_rank: int = 0
+
+    @property
+    def positions_per_rank(self) -> int:
+        """Chunks a rank buffer has room for."""
+        return self.slots_per_rank if self.slot is not None else self.num_chunks
 
     def descriptions(self, dtype: str, elems_per_chunk: int):
         """(Topology, Collective, Schedule) for sccl_plan_create."""
         return (sccl.Topology(self.num_nodes, self.bw),
-                sccl.Collective(self.num_chunks, self.pre, self.post, self.combining, dtype, elems_per_chunk),
+                sccl.Collective(self.num_chunks, self.pre, self.post, self.combining, dtype, elems_per_chunk,
+                                self.slot, self.slots_per_rank),
                 sccl.Schedule(self.rounds, self.sends))
 
 
@@ -91,6 +101,7 @@ def load(path_or_name: str) -> ScheduleFile:
     bw: List[Tuple[List[Tuple[int, int]], int]] = []
     rounds: List[int] = []
     sends = np.zeros((0, 5), dtype=np.int32)
+    slot, slots_per_rank = None, 0
     for ln in lines:
         w = ln.split()
         if w[0] == "name":
@@ -110,6 +121,9 @@ def load(path_or_name: str) -> ScheduleFile:
         elif w[0] == "bw":
             edges = [tuple(int(x) for x in e.split(">")) for e in w[2:]]
             bw.append((edges, int(w[1])))
+        elif w[0] == "slots":
+            slots_per_rank = int(w[1])
+            slot = np.array([[int(x) for x in next(lines).split()] for _ in range(G)], dtype=np.int32).reshape(G, P)
         elif w[0] == "rounds":
             rounds = [int(x) for x in w[1:]]
         elif w[0] == "sends":
@@ -117,4 +131,4 @@ def load(path_or_name: str) -> ScheduleFile:
             sends = np.array([[int(x) for x in next(lines).split()] for _ in range(n)], dtype=np.int32).reshape(-1, 5)
         else:
             raise ValueError(f"unknown record {w[0]}")
-    return ScheduleFile(name, collective, combining, P, G, C, pre, post, bw, rounds, sends)
+    return ScheduleFile(name, collective, combining, P, G, C, pre, post, bw, rounds, sends, slot, slots_per_rank)

@@ -15,8 +15,8 @@ class Workload:
     dtype: str               # i32 | f32 | f16
     dist: str                # inputs.generate distribution
     seed: int
-    bytes_per_rank: int
-    poison_non_owned: bool   # Allgather: chunks a rank does not own are undefined inputs
+    bytes_per_rank: int      # the whole rank buffer: every chunk position the layout gives a rank
+    poison_non_owned: bool   # non-combining collectives: positions a rank holds nothing in at the start are undefined inputs
 
     @property
     def elem_bytes(self) -> int:
@@ -35,6 +35,9 @@ WORKLOADS: Dict[str, Workload] = {
     # config 4: ring Allreduce fp16 (fp32 accumulation), 8 ranks x 512 MiB
     "cfg4": Workload("cfg4", "cfg4_allreduce_ring8", "f16", "normal", 4, 512 * MiB, False),
     "cfg4b": Workload("cfg4b", "cfg4b_allreduce_ring8_c2", "f16", "normal", 4, 512 * MiB, False),
+    # beyond the five configurations: Alltoall, the paper's row (8,3,3) on its DGX-1 graph; 8 ranks, 8 MiB chunks
+    # (a 64 MiB send buffer per rank) in a compact layout of 20 chunk positions per rank
+    "alltoall": Workload("alltoall", "alltoall_dgx1", "f32", "uniform", 6, 20 * 8 * MiB, True),
 }
 
 

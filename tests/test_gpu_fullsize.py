@@ -5,7 +5,7 @@ independent, so executing the schedule on the windows alone (same bits in, read 
 inputs before the run) must give the bits the GPU left in those windows.  Windows sit at the start of
 a chunk, across a tile boundary in the middle, and at the ragged end.  On top of that, properties that
 hold at any size are checked on the whole buffers: Allgather's closed form out[n][c] = in[c mod P][c],
-and all ranks bitwise equal after Allreduce.  Tolerance: 0 ulp (see test_gpu_parity.py).
+Alltoall's out[(c div P) mod P][c] = in[c mod P][c], and all ranks bitwise equal after Allreduce.  Tolerance: 0 ulp (see test_gpu_parity.py).
 """
 import numpy as np
 import pytest
@@ -18,7 +18,8 @@ from bench import make_inputs
 pytestmark = pytest.mark.gpu
 
 CASES = [("cfg2", workloads.WORKLOADS["cfg2"]), ("cfg3", workloads.WORKLOADS["cfg3"]),
-         ("cfg4", workloads.WORKLOADS["cfg4"]), ("cfg4b", workloads.WORKLOADS["cfg4b"])]
+         ("cfg4", workloads.WORKLOADS["cfg4"]), ("cfg4b", workloads.WORKLOADS["cfg4b"]),
+         ("alltoall", workloads.WORKLOADS["alltoall"])]
 for coll in ("allgather", "allreduce"):
     for size in (1 << 10, 1 << 16, 1 << 22, 1 << 28, 1 << 30):
         CASES.append((f"cfg5-{coll}-{size}", workloads.sweep_workload(coll, size)))
@@ -46,20 +47,26 @@ def test_full_size_sampled_windows_and_global_properties(label, wl):
     wins = windows(epc, tile_elems)
     wtot = sum(n for _, n in wins)
 
-    def gather(bufs):          # per rank: G chunks x the sampled windows, concatenated
+    K = sf.positions_per_rank                             # chunk positions of a rank buffer (G unless a layout is given)
+
+    def position(c, n):
+        return c if sf.slot is None else int(sf.slot[c, n])
+
+    def gather(bufs):          # per rank: K chunk positions x the sampled windows, concatenated
         out = []
         for b in bufs:
-            v = b.view(G, epc)
+            v = b.view(K, epc)
             out.append(torch.cat([v[:, s:s + n] for s, n in wins], dim=1).contiguous().cpu().numpy().reshape(-1))
         return out
 
     host = gather(work)                                   # the oracle's inputs: the same bits the GPU starts from
     owners = None
-    if sf.collective == "allgather":
-        owners = [work[c % P].view(G, epc)[c].clone() for c in range(G)]
+    if sf.collective in ("allgather", "alltoall"):         # both start Scattered: chunk c at rank c mod P
+        owners = [work[c % P].view(K, epc)[position(c, c % P)].clone() for c in range(G)]
     sccl.sccl_execute(plan, work)
     torch.cuda.synchronize()
-    ex.execute(wl.dtype, G, wtot, Schedule(sf.rounds, sf.sends), host, threads=8)
+    ex.execute(wl.dtype, G, wtot, Schedule(sf.rounds, sf.sends), host, threads=8,
+               slot=sf.slot, slots_per_rank=sf.slots_per_rank if sf.slot is not None else None)
     got = gather(work)
     u = np.uint32 if wl.elem_bytes == 4 else np.uint16
     for n in range(P):
@@ -70,6 +77,10 @@ def test_full_size_sampled_windows_and_global_properties(label, wl):
             v = work[n].view(G, epc)
             for c in range(G):
                 assert torch.equal(v[c], owners[c]), f"rank {n} chunk {c} is not the owner's chunk"
+    elif sf.collective == "alltoall":                      # Transpose: chunk c ends at rank (c div P) mod P
+        for c in range(G):
+            n = (c // P) % P
+            assert torch.equal(work[n].view(K, epc)[position(c, n)], owners[c]), f"chunk {c} did not arrive at rank {n}"
     else:
         ref = work[0].view(torch.int32 if wl.elem_bytes == 4 else torch.int16)
         for n in range(1, P):

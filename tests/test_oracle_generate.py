@@ -203,10 +203,19 @@ def test_stored_schedule_files_are_what_the_oracle_writes():
     import os
     from oracle import write_schedules as ws
     from paper_2008_08708_amd import schedule_file
-    for name, (topo, coll, sched) in ws.configurations().items():
+    every = dict(ws.configurations())
+    every.update(ws.extra_configurations())
+    lay = ws.layouts()
+    for name, (topo, coll, sched) in every.items():
         path = os.path.join(ws.OUT, name + ".txt")
-        assert open(path).read() == ws.render(name, topo, coll, sched), name
+        slot, per_rank = lay.get(name, (None, 0))
+        assert open(path).read() == ws.render(name, topo, coll, sched, slot, per_rank), name
         sf = schedule_file.load(name)                     # and the reader gives back the same plan
+        if slot is None:
+            assert sf.slot is None and sf.positions_per_rank == coll.num_chunks
+        else:
+            assert (sf.slot == slot).all() and sf.positions_per_rank == per_rank
+            assert validate(topo, coll, sched).ok
         assert (sf.num_nodes, sf.num_chunks, sf.rounds) == (coll.num_nodes, coll.num_chunks, sched.rounds)
         assert (sf.sends == sched.sends).all() and (sf.pre == coll.pre).all() and (sf.post == coll.post).all()
         assert sorted((sorted(L), b) for L, b in sf.bw) == sorted((sorted(L), b) for L, b in topo.bw)
