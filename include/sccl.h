@@ -48,7 +48,8 @@ typedef enum {
     SCCL_ERR_ALIGNMENT = 8,        /* a rank buffer is not 16-byte aligned */
     SCCL_ERR_OVERLAP = 9,          /* two rank buffers overlap */
     SCCL_ERR_NOMEM = 10,
-    SCCL_ERR_DEVICE = 11           /* a HIP call failed, or execute on a host-only plan */
+    SCCL_ERR_DEVICE = 11           /* a HIP call failed, execute on a host-only plan, or execute while another
+                                      device than the plan's is current */
 } sccl_status_t;
 
 typedef enum {

@@ -678,6 +678,8 @@ sccl_status_t sccl_plan_create(const sccl_topology_t* topology, const sccl_colle
 static sccl_status_t check_buffers(const sccl_plan_t* plan, void* const* rank_buffers) {
     if (!plan || !rank_buffers) return SCCL_ERR_INVALID_ARG;
     if (plan->device < 0) return SCCL_ERR_DEVICE;
+    int current = -1;                                    // the step tables live on the device the plan was made on
+    if (hipGetDevice(&current) != hipSuccess || current != plan->device) return SCCL_ERR_DEVICE;
     const int32_t P = plan->P;
     const uint64_t bytes = (uint64_t)plan->stats.bytes_per_rank;
     for (int32_t n = 0; n < P; n++) {

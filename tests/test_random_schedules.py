@@ -11,7 +11,10 @@ from oracle.validate import validate
 from paper_2008_08708_amd import inputs
 from random_cases import random_case
 
-SEEDS = list(range(100, 140))
+import os
+
+# 40 seeds by default; SCCL_MORE_SEEDS=N adds seeds 1000 .. 1000+N-1 for a longer soak of the same tests
+SEEDS = list(range(100, 140)) + list(range(1000, 1000 + int(os.environ.get("SCCL_MORE_SEEDS", "0"))))
 
 
 def make_inputs(coll, dtype, dist, seed, epc):
