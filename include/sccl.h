@@ -128,17 +128,18 @@ typedef struct {
 /* How sccl_execute lowers the plan (paper, section 4: the same schedule admits several lowerings).
  *   SCCL_LOWER_MEMORY  every send reads and writes the rank buffers; what one step wrote the next step
  *                      reads back through the cache hierarchy.  Work is split by (chunk, element tile).
- *   SCCL_LOWER_STAGED  a workgroup takes one element slice of EVERY chunk of EVERY rank, loads the cells
- *                      (rank, chunk position) the schedule reads into the local data share, runs all
- *                      sends there, dependency level by dependency level, and writes the cells the
- *                      schedule wrote back once.  Same operations in the same order per element, hence
- *                      the same bits; made for small buffers, where the time is the chain of memory
- *                      round trips (the latency term of the paper's cost model, section 3.6) and not the
- *                      bytes.  Needs room for one slice of every cell: SCCL_ERR_INVALID_ARG if asked
- *                      for explicitly and the cells do not fit.
- *   SCCL_LOWER_AUTO    staged when the cells fit and the P rank buffers together are at most 512 KiB
- *                      (the measured crossover: below it the time is launch plus latency and no
- *                      bandwidth claim applies), through memory otherwise. */
+ *   SCCL_LOWER_STAGED  a workgroup takes one slice (a run of consecutive vectors) of one chunk, loads it from
+ *                      every cell (rank, chunk position) of that chunk the schedule reads into the local
+ *                      data share, runs all the chunk's sends there, dependency level by dependency level,
+ *                      and writes the cells the schedule wrote back once.  Same operations in the same
+ *                      order per element, hence the same bits; made for small buffers, where the time is
+ *                      the chain of memory round trips (the latency term of the paper's cost model, section
+ *                      3.6) and not the bytes.  Needs room for one slice of every cell of a chunk and fewer
+ *                      than 256 dependency levels per chunk: SCCL_ERR_INVALID_ARG if asked for explicitly
+ *                      and that does not hold.
+ *   SCCL_LOWER_AUTO    staged when possible and the P rank buffers together are at most 16 MiB (the measured
+ *                      crossover: below it the time is launch plus latency and no bandwidth claim applies),
+ *                      through memory otherwise. */
 #define SCCL_LOWER_AUTO   0
 #define SCCL_LOWER_MEMORY 1
 #define SCCL_LOWER_STAGED 2
@@ -150,9 +151,9 @@ typedef struct {
     int32_t max_workgroups;        /* 0 = choose (through memory: one workgroup per compute unit); else the
                                       grid size of either kernel; always capped by the number of work items */
     int32_t lowering;              /* SCCL_LOWER_* */
-    int32_t slice_vectors;         /* staged kernel: 0 = choose; else a power of two: vectors of every cell a
-                                      workgroup stages at a time */
-    int32_t staged_threads;        /* staged kernel: 0 = choose; else 64, 128, 256, 512 or 1024 */
+    int32_t slice_vectors;         /* staged kernel: 0 = choose; else a power of two: vectors of every cell of a chunk
+                                      a workgroup stages at a time */
+    int32_t staged_threads;        /* staged kernel: 0 = one wavefront (64); else 64, 128, 256, 512 or 1024 */
     int32_t reserved;              /* must be 0 */
 } sccl_options_t;
 
@@ -177,15 +178,15 @@ typedef struct {
     int32_t grid_workgroups;       /* grid of the kernel sccl_execute launches; 0 for a host-only plan */
     /* the staged lowering: dependency structure of the schedule and what a workgroup stages */
     int32_t lowering;              /* SCCL_LOWER_MEMORY or SCCL_LOWER_STAGED: what sccl_execute runs */
-    int32_t staged_available;      /* 1 if one slice of every cell fits the local data share */
-    int32_t num_cells;             /* distinct (rank, chunk position) pairs some send touches */
+    int32_t staged_available;      /* 1 if one slice of every cell of a chunk fits the local data share */
+    int32_t num_cells;             /* distinct (rank, chunk position) pairs some send touches, over all chunks */
     int32_t num_cells_loaded;      /* of those, read before any send writes them */
     int32_t num_cells_stored;      /* of those, written by some send */
-    int32_t num_levels;            /* length of the longest chain of dependent groups */
-    int32_t max_level_tasks;       /* most cell writes any one level performs */
+    int32_t num_levels;            /* length of the longest chain of dependent groups (of any one chunk) */
+    int32_t max_level_tasks;       /* most cell writes any one level of any one chunk performs */
     int32_t slice_vectors, staged_threads;
     int32_t staged_lds_bytes;      /* local data share one workgroup uses */
-    int64_t num_slices;            /* staged work items: ceil(vectors per chunk / slice_vectors) */
+    int64_t num_slices;            /* staged work items: G * ceil(vectors per chunk / slice_vectors) */
 } sccl_stats_t;
 
 typedef struct sccl_plan sccl_plan_t;

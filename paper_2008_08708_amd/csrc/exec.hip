@@ -331,23 +331,22 @@ __global__ void __launch_bounds__(256) copy16_kernel(u32x4* __restrict__ dst, co
 
 
 // ---- the staged lowering -----------------------------------------------------------------------
-// A work item is an element *slice*: the same `slice` vectors of every chunk of every rank.  The
-// workgroup (1) loads the slice of every cell the schedule reads before writing into the local data
-// share, all loads in flight together: one memory round trip; (2) runs the schedule there, one
-// dependency level after the other with a workgroup barrier in between, one lane per (cell write,
-// vector); (3) stores the slice of every cell the schedule wrote.  Per element the operations and their
-// order are those of the schedule, so the bits equal the other lowerings'.  The chain of a chunk's
-// sends costs local-memory latency per level instead of a cache round trip per group, which is what
-// small buffers are bound by.
+// A work item is (chunk, slice): `slice` consecutive vectors of the chunk, in every rank buffer that holds
+// it.  The workgroup (1) loads the slice of every cell of the chunk that the schedule reads before writing
+// into the local data share, all loads in flight together: one memory round trip; (2) runs the chunk's
+// sends there, one dependency level after the other, one lane per (cell write, vector), with a workgroup
+// barrier between levels (nothing but program order when the workgroup is a single wavefront); (3) stores
+// the slice of every cell the schedule wrote.  Per element the operations and their order are those of the
+// schedule, so the bits equal the other lowerings'.  A chunk's chain of sends costs local-memory latency
+// per level instead of a cache round trip per group, which is what small buffers are bound by.
 struct StagedArgs {
-    const int32_t* table;         // see plan.hpp
+    const int32_t* table;         // per-chunk headers and blocks, see plan.hpp
     int64_t chunk_bytes;
-    int64_t num_slices;
+    int64_t num_items;            // chunks x slices per chunk
     int64_t vecs_per_chunk;
-    int32_t n_in, n_out, n_levels, table_words;
-    int32_t off_out, off_lev, off_task, off_srcs;
+    int64_t slices_per_chunk;
     int32_t log_slice;            // vectors per slice = 1 << log_slice
-    int32_t max_level_tasks;      // tasks of the widest level
+    int32_t block_words;          // room for the largest chunk block, in words (a multiple of 4)
     char* bufs[SCCL_MAX_RANKS];
 };
 
@@ -357,28 +356,31 @@ __device__ __forceinline__ char* rank_base(uint32_t lo, uint32_t hi, int32_t ran
     return (char*)(((uint64_t)h << 32) | l);
 }
 
+// Offsets of the parts of one chunk's block inside the local copy, and their sizes.
+struct StagedBlock { int32_t n_in, n_out, n_levels, off_out, off_lev, off_task, off_srcs, max_level; };
+
 // One task as a lane holds it: the two table words (t0 < 0: no task) and, for a reduce task, its
 // first four source cells.
 struct StagedTask { int32_t t0, t1, s[4]; };
 
-__device__ __forceinline__ void fetch_words(StagedTask& t, const int32_t* tab, const StagedArgs& a,
+__device__ __forceinline__ void fetch_words(StagedTask& t, const int32_t* tab, const StagedBlock& b,
                                             int32_t t_lo, int32_t t_hi, int32_t i, int32_t ls) {
     const int32_t task = t_lo + (i >> ls);
     t.t0 = -1; t.t1 = 0;
     if (task < t_hi) {
-        t.t0 = tab[a.off_task + 2 * task];
-        t.t1 = tab[a.off_task + 2 * task + 1];
+        t.t0 = tab[b.off_task + 2 * task];
+        t.t1 = tab[b.off_task + 2 * task + 1];
     }
 }
-__device__ __forceinline__ void fetch_sources(StagedTask& t, const int32_t* tab, const StagedArgs& a) {
+__device__ __forceinline__ void fetch_sources(StagedTask& t, const int32_t* tab, const StagedBlock& b) {
     if (t.t0 >= (1 << 16)) {                                       // a reduce task; the list is padded by three words
 #pragma unroll
-        for (int j = 0; j < 4; j++) t.s[j] = tab[a.off_srcs + t.t1 + j];
+        for (int j = 0; j < 4; j++) t.s[j] = tab[b.off_srcs + t.t1 + j];
     }
 }
 
 template <int DT, int W>
-__device__ __forceinline__ void run_task(typename VecOf<W>::type* cells, const int32_t* tab, const StagedArgs& a,
+__device__ __forceinline__ void run_task(typename VecOf<W>::type* cells, const int32_t* tab, const StagedBlock& b,
                                          const StagedTask& t, int32_t v, int32_t ls) {
     typedef typename VecOf<W>::type V;
     if (t.t0 < 0) return;
@@ -398,7 +400,7 @@ __device__ __forceinline__ void run_task(typename VecOf<W>::type* cells, const i
 #pragma unroll
     for (int j = 0; j < 4; j++)
         if (j < k) acc.add(x[j]);
-    for (int32_t j = 4; j < k; j++) acc.add(cells[(tab[a.off_srcs + t.t1 + j] << ls) + v]);
+    for (int32_t j = 4; j < k; j++) acc.add(cells[(tab[b.off_srcs + t.t1 + j] << ls) + v]);
     cells[(dst << ls) + v] = acc.template done<V>();
 }
 
@@ -411,50 +413,70 @@ __device__ __forceinline__ int32_t level_first(const int32_t (&reg)[4], int32_t 
     return __builtin_amdgcn_readlane(r, l & 63);
 }
 
+// Orders this workgroup's local-memory accesses before and after: a barrier, or for a single wavefront
+// (whose local-memory operations execute in program order) only a fence for the compiler.
+__device__ __forceinline__ void staged_sync(bool one_wave) {
+    if (one_wave) __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    else __syncthreads();
+}
+
 template <int DT, int W>
 __global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
     typedef typename VecOf<W>::type V;
     extern __shared__ __attribute__((aligned(16))) unsigned char staged_lds[];
-    const int32_t* tab = (const int32_t*)staged_lds;
-    V* cells = (V*)(staged_lds + (size_t)a.table_words * 4);      // table_words is a multiple of 4
+    const int32_t* tab = (const int32_t*)staged_lds;               // the chunk's block
+    V* cells = (V*)(staged_lds + (size_t)a.block_words * 4);
     const int32_t tid = (int32_t)threadIdx.x, BT = (int32_t)blockDim.x;
+    const bool one_wave = BT <= 64;
     const int32_t ls = a.log_slice, sv = 1 << ls, vmask = sv - 1;
+    table_ptr gt = (table_ptr)a.table;                             // scalar loads of the header
 
-    // lane n of every wavefront keeps the base pointer of rank n (P <= 64 = lanes of a wavefront) ...
+    // lane n of every wavefront keeps the base pointer of rank n (P <= 64 = lanes of a wavefront)
     const uint64_t mine = (uint64_t)a.bufs[tid & 63];
     const uint32_t base_lo = (uint32_t)mine, base_hi = (uint32_t)(mine >> 32);
-    // ... and the level table (at most 256 entries), so that level bounds cost no memory access
-    int32_t levreg[4];
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-        const int32_t l = (tid & 63) + 64 * q;
-        levreg[q] = a.table[a.off_lev + (l < a.n_levels ? l : a.n_levels)];
-    }
-
-    // the tables go to the local data share once per workgroup, 16 bytes per lane and trip
-    {
-        const u32x4* src = (const u32x4*)a.table;
-        u32x4* dst = (u32x4*)staged_lds;
-        for (int32_t i = tid; i < a.table_words / 4; i += BT) dst[i] = src[i];
-    }
 
     constexpr int UA = 4;                                          // loads a lane keeps in flight in phase 1
-    const int32_t in_lanes = a.n_in << ls, out_lanes = a.n_out << ls;
-    for (int64_t slice = blockIdx.x; slice < a.num_slices; slice += gridDim.x) {
+    for (int64_t item = blockIdx.x; item < a.num_items; item += gridDim.x) {
+        const int32_t c = (int32_t)(item / a.slices_per_chunk);
+        const int64_t slice = item - (int64_t)c * a.slices_per_chunk;
         const int64_t v0 = slice << ls;
         const int64_t left = a.vecs_per_chunk - v0;
         const int32_t here = left < sv ? (int32_t)left : sv;       // vectors of this slice that exist
         const int64_t slice_off = v0 * W;
         const bool live = (tid & vmask) < here;                    // this lane's vector exists in this slice
 
+        // the chunk's header (the same in every lane) and its block
+        table_ptr h = gt + (int64_t)c * STAGED_HEADER_WORDS;
+        const int32_t blk = h[0], n_cells = h[1], n_tasks = h[5], words = h[7];
+        StagedBlock b;
+        b.n_in = h[2]; b.n_out = h[3]; b.n_levels = h[4];
+        b.off_out = n_cells;
+        b.off_lev = b.off_out + 2 * b.n_out;
+        b.off_task = b.off_lev + b.n_levels + 2;
+        b.off_srcs = b.off_task + 2 * n_tasks;
+        const int32_t* gblock = a.table + blk;
+        // the level table (at most 256 entries) goes to registers, so that level bounds cost no memory access
+        int32_t levreg[4];
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const int32_t l = (tid & 63) + 64 * q;
+            levreg[q] = gblock[b.off_lev + (l < b.n_levels ? l : b.n_levels)];
+        }
+        {   // the block goes to the local data share, 16 bytes per lane and trip
+            const u32x4* src = (const u32x4*)gblock;
+            u32x4* dst = (u32x4*)staged_lds;
+            for (int32_t i = tid; i < words / 4; i += BT) dst[i] = src[i];
+        }
+
         // ---- (1) load: cell i < n_in is the i-th loaded cell; its operand word comes straight from memory
+        const int32_t in_lanes = b.n_in << ls, out_lanes = b.n_out << ls;
         for (int32_t base = 0; base < in_lanes; base += BT * UA) {
             int32_t w[UA]; bool ok[UA]; V x[UA];
 #pragma unroll
             for (int u = 0; u < UA; u++) {
                 const int32_t i = base + u * BT + tid;
                 ok[u] = i < in_lanes && (i & vmask) < here;
-                w[u] = ok[u] ? a.table[i >> ls] : 0;
+                w[u] = ok[u] ? gblock[i >> ls] : 0;
             }
 #pragma unroll
             for (int u = 0; u < UA; u++) {
@@ -469,40 +491,34 @@ __global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
                 if (ok[u]) cells[i] = x[u];                        // cell (i >> ls), vector (i & vmask)
             }
         }
-        __syncthreads();
+        staged_sync(one_wave);
 
-        // ---- (2) the schedule, level by level.  The tables are read-only, so a lane fetches its task of the
+        // ---- (2) the schedule, level by level.  The block is read-only, so a lane fetches its task of the
         // NEXT level (two words, then a reduce task's sources) while the cells of the current level are on
-        // their way; wavefronts beyond the widest level only take part in the barriers.
-        // The first cell this lane stores in phase 3, (cell id, operand word), is fetched here as well.
+        // their way.  The first cell this lane stores in phase 3, (cell id, operand word), is fetched here too.
         const bool ok0 = tid < out_lanes && live;
-        const int32_t out_c0 = ok0 ? tab[a.off_out + 2 * (tid >> ls)] : 0;
-        const int32_t out_w0 = ok0 ? tab[a.off_out + 2 * (tid >> ls) + 1] : 0;
-        const bool wave_works = (tid & ~63) < (a.max_level_tasks << ls);      // the same in every lane of a wavefront
-        int32_t lo0 = level_first(levreg, 0, a.n_levels), lo1 = level_first(levreg, 1, a.n_levels);
+        const int32_t out_c0 = ok0 ? tab[b.off_out + 2 * (tid >> ls)] : 0;
+        const int32_t out_w0 = ok0 ? tab[b.off_out + 2 * (tid >> ls) + 1] : 0;
+        int32_t lo0 = level_first(levreg, 0, b.n_levels), lo1 = level_first(levreg, 1, b.n_levels);
         StagedTask cur;
-        if (wave_works) {
-            fetch_words(cur, tab, a, lo0, lo1, tid, ls);
-            fetch_sources(cur, tab, a);
-        }
-        for (int32_t lv = 0; lv < a.n_levels; lv++) {
-            const int32_t lo2 = level_first(levreg, lv + 2, a.n_levels);
-            if (wave_works) {
-                StagedTask nxt;
-                fetch_words(nxt, tab, a, lo1, lo2, tid, ls);
-                if (live) run_task<DT, W>(cells, tab, a, cur, tid & vmask, ls);
-                fetch_sources(nxt, tab, a);
-                const int32_t lanes = (lo1 - lo0) << ls;
-                for (int32_t i = tid + BT; i < lanes; i += BT) {   // levels wider than the workgroup
-                    if ((i & vmask) >= here) continue;
-                    StagedTask t;
-                    fetch_words(t, tab, a, lo0, lo1, i, ls);
-                    fetch_sources(t, tab, a);
-                    run_task<DT, W>(cells, tab, a, t, i & vmask, ls);
-                }
-                cur = nxt;
+        fetch_words(cur, tab, b, lo0, lo1, tid, ls);
+        fetch_sources(cur, tab, b);
+        for (int32_t lv = 0; lv < b.n_levels; lv++) {
+            const int32_t lo2 = level_first(levreg, lv + 2, b.n_levels);
+            StagedTask nxt;
+            fetch_words(nxt, tab, b, lo1, lo2, tid, ls);
+            if (live) run_task<DT, W>(cells, tab, b, cur, tid & vmask, ls);
+            fetch_sources(nxt, tab, b);
+            const int32_t lanes = (lo1 - lo0) << ls;
+            for (int32_t i = tid + BT; i < lanes; i += BT) {       // levels wider than the workgroup
+                if ((i & vmask) >= here) continue;
+                StagedTask t;
+                fetch_words(t, tab, b, lo0, lo1, i, ls);
+                fetch_sources(t, tab, b);
+                run_task<DT, W>(cells, tab, b, t, i & vmask, ls);
             }
-            __syncthreads();
+            cur = nxt;
+            staged_sync(one_wave);
             lo0 = lo1; lo1 = lo2;
         }
 
@@ -510,13 +526,13 @@ __global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
         for (int32_t base = 0; base < out_lanes; base += BT) {
             const int32_t i = base + tid;
             const bool ok = i < out_lanes && (i & vmask) < here;
-            const int32_t c = base == 0 ? out_c0 : (ok ? tab[a.off_out + 2 * (i >> ls)] : 0);
-            const int32_t w = base == 0 ? out_w0 : (ok ? tab[a.off_out + 2 * (i >> ls) + 1] : 0);
-            char* p = rank_base(base_lo, base_hi, w & OPERAND_RANK_MASK) +
-                      (int64_t)(w >> OPERAND_RANK_BITS) * a.chunk_bytes + slice_off + (int64_t)(i & vmask) * W;
-            if (ok) *(V*)p = cells[(c << ls) + (i & vmask)];
+            const int32_t oc = base == 0 ? out_c0 : (ok ? tab[b.off_out + 2 * (i >> ls)] : 0);
+            const int32_t ow = base == 0 ? out_w0 : (ok ? tab[b.off_out + 2 * (i >> ls) + 1] : 0);
+            char* p = rank_base(base_lo, base_hi, ow & OPERAND_RANK_MASK) +
+                      (int64_t)(ow >> OPERAND_RANK_BITS) * a.chunk_bytes + slice_off + (int64_t)(i & vmask) * W;
+            if (ok) *(V*)p = cells[(oc << ls) + (i & vmask)];
         }
-        if (slice + gridDim.x < a.num_slices) __syncthreads();     // the next slice overwrites the cells
+        if (item + gridDim.x < a.num_items) staged_sync(one_wave); // the next item overwrites the block and the cells
     }
 }
 
@@ -651,10 +667,9 @@ sccl_status_t sccl_plan_create_ex(const sccl_topology_t* topology, const sccl_co
                 hipMalloc((void**)&plan->d_staged, tb) == hipSuccess &&
                 hipMemcpy(plan->d_staged, sg.table.data(), tb, hipMemcpyHostToDevice) == hipSuccess;
             if (!staged_ok) { sccl_plan_destroy(plan); return SCCL_ERR_DEVICE; }
-            // as many workgroups per CU as its local data share and its 2048 lanes hold, at most 8
-            int64_t per_cu = std::min<int64_t>(STAGED_LDS_LIMIT / sg.lds_bytes, 2048 / sg.threads);
-            per_cu = std::max<int64_t>(1, std::min<int64_t>(per_cu, 8));
-            int64_t sgrid = plan->opts.max_workgroups > 0 ? plan->opts.max_workgroups : num_cus * per_cu;
+            // Latency bound: one workgroup per work item while the hardware can queue them (32 per CU), the
+            // grid-stride loop only beyond that
+            int64_t sgrid = plan->opts.max_workgroups > 0 ? plan->opts.max_workgroups : (int64_t)num_cus * 32;
             if (sgrid > sg.num_slices) sgrid = sg.num_slices;
             sg.grid = (int32_t)sgrid;
         }
@@ -739,13 +754,11 @@ static sccl_status_t launch_staged(const sccl_plan_t* plan, void* const* rank_bu
     std::memset(&args, 0, sizeof(args));
     args.table = plan->d_staged;
     args.chunk_bytes = plan->stats.chunk_bytes;
-    args.num_slices = sg.num_slices;
+    args.num_items = sg.num_slices;
     args.vecs_per_chunk = plan->vecs_per_chunk;
-    args.n_in = sg.n_in; args.n_out = sg.n_out; args.n_levels = sg.n_levels;
-    args.table_words = (int32_t)sg.table.size();
-    args.off_out = sg.off_out; args.off_lev = sg.off_lev; args.off_task = sg.off_task; args.off_srcs = sg.off_srcs;
+    args.slices_per_chunk = sg.slices_per_chunk;
     args.log_slice = sg.log_slice_vectors;
-    args.max_level_tasks = sg.max_level_tasks;
+    args.block_words = sg.max_block_words;
     for (int32_t n = 0; n < plan->P; n++) args.bufs[n] = (char*)rank_buffers[n];
     staged_fn fn = pick_staged_kernel(plan->dtype, plan->vector_bytes);
     hipLaunchKernelGGL(fn, dim3((unsigned)sg.grid), dim3((unsigned)sg.threads), (size_t)sg.lds_bytes, (hipStream_t)stream, args);

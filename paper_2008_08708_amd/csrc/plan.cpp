@@ -28,103 +28,126 @@ struct Group {
 
 int elem_bytes(sccl_dtype_t d) { return d == SCCL_F16 ? 2 : 4; }
 
-// Tables of the staged lowering from the groups in step order (plan->step_prog): cells, levels, tasks.
-// Returns false when the schedule has more cells than a task word can name.
+// Tables of the staged lowering: one block per chunk, from the chunk's op list in step order (plan.prog).
+// Returns false when some chunk has more levels than the kernel keeps in registers.
 bool build_staged_tables(const sccl_plan& plan, sccl_staged* out) {
     sccl_staged& sg = *out;
     sg = sccl_staged();
-    const std::vector<int32_t>& prog = plan.step_prog;
-    const size_t n_groups = plan.group_off.size();
-    // pass 1: the cells, and which of them are read before they are written
-    std::map<int32_t, int32_t> first_access;              // operand word -> 0 read first, 1 written first
-    std::vector<int32_t> order;                           // operand words by first appearance
-    auto touch = [&](int32_t w, int32_t how) {
-        if (first_access.emplace(w, how).second) order.push_back(w);
-    };
-    for (size_t g = 0; g < n_groups; g++) {
-        const int32_t* op = &prog[(size_t)plan.group_off[g]];
-        const int32_t k = op[0] >> 8;
-        if (op[0] & OP_KIND_REDUCE) {
-            touch(op[1], 0);                              // the destination's own value is the first operand
-            for (int32_t j = 0; j < k; j++) touch(op[2 + j], 0);
-        } else {
-            touch(op[1], 0);
-            for (int32_t j = 0; j < k; j++) touch(op[2 + j], 1);
+    const int32_t G = plan.G;
+    std::vector<int32_t> header((size_t)G * STAGED_HEADER_WORDS, 0), blocks;
+    for (int32_t c = 0; c < G; c++) {
+        // the chunk's groups: (pointer to header word) in step order
+        std::vector<const int32_t*> groups;
+        for (int32_t w = plan.chunk_off[(size_t)c]; w < plan.chunk_off[(size_t)c + 1];) {
+            groups.push_back(&plan.prog[(size_t)w]);
+            w += 2 + (plan.prog[(size_t)w] >> 8);
         }
-    }
-    if (order.size() >= (size_t)STAGED_MAX_CELLS) return false;
-    std::map<int32_t, int32_t> cell;                      // operand word -> cell id, loaded cells first
-    std::vector<int32_t> cell_word;
-    for (int pass = 0; pass < 2; pass++)
-        for (int32_t w : order)
-            if (first_access[w] == pass) { cell[w] = (int32_t)cell_word.size(); cell_word.push_back(w); }
-    sg.n_cells = (int32_t)cell_word.size();
-    for (int32_t w : order) sg.n_in += first_access[w] == 0;
-
-    // pass 2: levels.  wl/rl: level of the last write of a cell / highest level that read it.
-    std::vector<int32_t> wl((size_t)sg.n_cells, 0), rl((size_t)sg.n_cells, 0), level(n_groups, 0);
-    std::vector<uint8_t> written((size_t)sg.n_cells, 0);
-    int32_t n_levels = 0;
-    for (size_t g = 0; g < n_groups; g++) {
-        const int32_t* op = &prog[(size_t)plan.group_off[g]];
-        const int32_t k = op[0] >> 8;
-        const bool reduce = (op[0] & OP_KIND_REDUCE) != 0;
-        const int32_t anchor = cell[op[1]];
-        int32_t lv = 1;
-        if (reduce) {
-            // reads the destination and the sources, writes the destination (its own read is no conflict)
-            lv = std::max(lv, std::max(wl[(size_t)anchor], rl[(size_t)anchor]) + 1);
-            for (int32_t j = 0; j < k; j++) lv = std::max(lv, wl[(size_t)cell[op[2 + j]]] + 1);
-        } else {
-            lv = std::max(lv, wl[(size_t)anchor] + 1);
-            for (int32_t j = 0; j < k; j++) {
-                const int32_t d = cell[op[2 + j]];
-                lv = std::max(lv, std::max(wl[(size_t)d], rl[(size_t)d]) + 1);
-            }
-        }
-        level[g] = lv;
-        n_levels = std::max(n_levels, lv);
-        if (reduce) {
-            for (int32_t j = 0; j < k; j++) { int32_t& r = rl[(size_t)cell[op[2 + j]]]; r = std::max(r, lv); }
-            wl[(size_t)anchor] = lv; written[(size_t)anchor] = 1;
-        } else {
-            rl[(size_t)anchor] = std::max(rl[(size_t)anchor], lv);
-            for (int32_t j = 0; j < k; j++) { const int32_t d = cell[op[2 + j]]; wl[(size_t)d] = lv; written[(size_t)d] = 1; }
-        }
-    }
-    sg.n_levels = n_levels;
-
-    // pass 3: the tasks, level by level, groups in step order inside a level
-    std::vector<int32_t> out_cells, lev_first((size_t)n_levels + 1, 0), tasks, srcs;
-    for (int32_t c = 0; c < sg.n_cells; c++)
-        if (written[(size_t)c]) { out_cells.push_back(c); out_cells.push_back(cell_word[(size_t)c]); }
-    for (int32_t lv = 1; lv <= n_levels; lv++) {
-        lev_first[(size_t)lv - 1] = (int32_t)(tasks.size() / 2);
-        for (size_t g = 0; g < n_groups; g++) {
-            if (level[g] != lv) continue;
-            const int32_t* op = &prog[(size_t)plan.group_off[g]];
+        const size_t n_groups = groups.size();
+        // pass 1: the cells, and which of them are read before they are written
+        std::map<int32_t, int32_t> first_access;          // operand word -> 0 read first, 1 written first
+        std::vector<int32_t> order;                       // operand words by first appearance
+        auto touch = [&](int32_t w, int32_t how) {
+            if (first_access.emplace(w, how).second) order.push_back(w);
+        };
+        for (const int32_t* op : groups) {
             const int32_t k = op[0] >> 8;
-            if (op[0] & OP_KIND_REDUCE) {
-                tasks.push_back(cell[op[1]] | (k << 16));
-                tasks.push_back((int32_t)srcs.size());
-                for (int32_t j = 0; j < k; j++) srcs.push_back(cell[op[2 + j]]);
+            const bool reduce = (op[0] & OP_KIND_REDUCE) != 0;
+            touch(op[1], 0);                              // copy: the source; reduce: the destination's own value
+            for (int32_t j = 0; j < k; j++) touch(op[2 + j], reduce ? 0 : 1);
+        }
+        std::map<int32_t, int32_t> cell;                  // operand word -> cell id, loaded cells first
+        std::vector<int32_t> cell_word;
+        int32_t n_in = 0;
+        for (int pass = 0; pass < 2; pass++)
+            for (int32_t w : order)
+                if (first_access[w] == pass) { cell[w] = (int32_t)cell_word.size(); cell_word.push_back(w); n_in += pass == 0; }
+        const int32_t n_cells = (int32_t)cell_word.size();
+
+        // pass 2: levels.  wl/rl: level of the last write of a cell / highest level that read it.
+        std::vector<int32_t> wl((size_t)n_cells, 0), rl((size_t)n_cells, 0), level(n_groups, 0);
+        std::vector<uint8_t> written((size_t)n_cells, 0);
+        int32_t n_levels = 0;
+        for (size_t g = 0; g < n_groups; g++) {
+            const int32_t* op = groups[g];
+            const int32_t k = op[0] >> 8;
+            const bool reduce = (op[0] & OP_KIND_REDUCE) != 0;
+            const int32_t anchor = cell[op[1]];
+            int32_t lv = 1;
+            if (reduce) {
+                // reads the destination and the sources, writes the destination (its own read is no conflict)
+                lv = std::max(lv, std::max(wl[(size_t)anchor], rl[(size_t)anchor]) + 1);
+                for (int32_t j = 0; j < k; j++) lv = std::max(lv, wl[(size_t)cell[op[2 + j]]] + 1);
             } else {
-                for (int32_t j = 0; j < k; j++) { tasks.push_back(cell[op[2 + j]]); tasks.push_back(cell[op[1]]); }
+                lv = std::max(lv, wl[(size_t)anchor] + 1);
+                for (int32_t j = 0; j < k; j++) {
+                    const int32_t d = cell[op[2 + j]];
+                    lv = std::max(lv, std::max(wl[(size_t)d], rl[(size_t)d]) + 1);
+                }
+            }
+            level[g] = lv;
+            n_levels = std::max(n_levels, lv);
+            if (reduce) {
+                for (int32_t j = 0; j < k; j++) { int32_t& r = rl[(size_t)cell[op[2 + j]]]; r = std::max(r, lv); }
+                wl[(size_t)anchor] = lv; written[(size_t)anchor] = 1;
+            } else {
+                rl[(size_t)anchor] = std::max(rl[(size_t)anchor], lv);
+                for (int32_t j = 0; j < k; j++) { const int32_t d = cell[op[2 + j]]; wl[(size_t)d] = lv; written[(size_t)d] = 1; }
             }
         }
-        sg.max_level_tasks = std::max(sg.max_level_tasks, (int32_t)(tasks.size() / 2) - lev_first[(size_t)lv - 1]);
+        if (n_levels >= STAGED_MAX_LEVELS) return false;
+
+        // pass 3: the tasks, level by level, groups in step order inside a level
+        std::vector<int32_t> out_cells, lev_first((size_t)n_levels + 1, 0), tasks, srcs;
+        for (int32_t i = 0; i < n_cells; i++)
+            if (written[(size_t)i]) { out_cells.push_back(i); out_cells.push_back(cell_word[(size_t)i]); }
+        int32_t widest = 0;
+        for (int32_t lv = 1; lv <= n_levels; lv++) {
+            lev_first[(size_t)lv - 1] = (int32_t)(tasks.size() / 2);
+            for (size_t g = 0; g < n_groups; g++) {
+                if (level[g] != lv) continue;
+                const int32_t* op = groups[g];
+                const int32_t k = op[0] >> 8;
+                if (op[0] & OP_KIND_REDUCE) {
+                    tasks.push_back(cell[op[1]] | (k << 16));
+                    tasks.push_back((int32_t)srcs.size());
+                    for (int32_t j = 0; j < k; j++) srcs.push_back(cell[op[2 + j]]);
+                } else {
+                    for (int32_t j = 0; j < k; j++) { tasks.push_back(cell[op[2 + j]]); tasks.push_back(cell[op[1]]); }
+                }
+            }
+            widest = std::max(widest, (int32_t)(tasks.size() / 2) - lev_first[(size_t)lv - 1]);
+        }
+        lev_first[(size_t)n_levels] = (int32_t)(tasks.size() / 2);
+        lev_first.push_back(lev_first.back());            // the kernel reads one level ahead
+        const int32_t n_srcs = (int32_t)srcs.size();
+        srcs.insert(srcs.end(), 3, 0);                    // and four sources at a time
+
+        // the block: cell words | stored cells | level table | tasks | sources, padded to whole 16-byte vectors
+        int32_t* h = &header[(size_t)c * STAGED_HEADER_WORDS];
+        h[0] = (int32_t)blocks.size();                    // relative to the end of the headers; fixed up below
+        h[1] = n_cells; h[2] = n_in; h[3] = (int32_t)(out_cells.size() / 2); h[4] = n_levels;
+        h[5] = (int32_t)(tasks.size() / 2); h[6] = n_srcs;
+        const size_t before = blocks.size();
+        blocks.insert(blocks.end(), cell_word.begin(), cell_word.end());
+        blocks.insert(blocks.end(), out_cells.begin(), out_cells.end());
+        blocks.insert(blocks.end(), lev_first.begin(), lev_first.end());
+        blocks.insert(blocks.end(), tasks.begin(), tasks.end());
+        blocks.insert(blocks.end(), srcs.begin(), srcs.end());
+        while (blocks.size() % 4) blocks.push_back(0);
+        h[7] = (int32_t)(blocks.size() - before);
+
+        sg.n_cells += n_cells; sg.n_in += n_in; sg.n_out += h[3]; sg.n_tasks += h[5];
+        sg.n_levels = std::max(sg.n_levels, n_levels);
+        sg.max_level_tasks = std::max(sg.max_level_tasks, widest);
+        sg.max_chunk_cells = std::max(sg.max_chunk_cells, n_cells);
+        sg.max_chunk_in = std::max(sg.max_chunk_in, n_in);
+        sg.max_chunk_out = std::max(sg.max_chunk_out, h[3]);
+        sg.max_block_words = std::max(sg.max_block_words, h[7]);
     }
-    lev_first[(size_t)n_levels] = (int32_t)(tasks.size() / 2);
-    sg.n_tasks = (int32_t)(tasks.size() / 2);
-    lev_first.push_back(lev_first.back());                // the kernel reads one level ahead
-    srcs.insert(srcs.end(), 3, 0);                        // and four sources at a time
-    sg.n_out = (int32_t)(out_cells.size() / 2);
-    sg.table = cell_word;
-    sg.off_out = (int32_t)sg.table.size();  sg.table.insert(sg.table.end(), out_cells.begin(), out_cells.end());
-    sg.off_lev = (int32_t)sg.table.size();  sg.table.insert(sg.table.end(), lev_first.begin(), lev_first.end());
-    sg.off_task = (int32_t)sg.table.size(); sg.table.insert(sg.table.end(), tasks.begin(), tasks.end());
-    sg.off_srcs = (int32_t)sg.table.size(); sg.table.insert(sg.table.end(), srcs.begin(), srcs.end());
-    while (sg.table.size() % 4) sg.table.push_back(0);   // whole 16-byte vectors
+    const int32_t base = (int32_t)header.size();         // G * 8 words: a multiple of 4
+    for (int32_t c = 0; c < G; c++) header[(size_t)c * STAGED_HEADER_WORDS] += base;
+    sg.table = header;
+    sg.table.insert(sg.table.end(), blocks.begin(), blocks.end());
     return true;
 }
 
@@ -427,30 +450,29 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
     // ---- the staged lowering: tables, then the slice a workgroup stages at a time
     sccl_staged& sg = plan->staged;
     const int32_t want_lowering = opts ? opts->lowering : SCCL_LOWER_AUTO;
-    if (build_staged_tables(*plan, &sg) && sg.n_tasks > 0 && sg.n_levels < STAGED_MAX_LEVELS && plan->vecs_per_chunk > 0) {
-        const int64_t table_bytes = (int64_t)sg.table.size() * 4;
-        const int64_t room = STAGED_LDS_LIMIT - table_bytes;                 // bytes left for the cells
-        const int64_t max_slice = room > 0 ? room / ((int64_t)sg.n_cells * W) : 0;   // vectors per cell that fit
+    if (build_staged_tables(*plan, &sg) && sg.n_tasks > 0 && plan->vecs_per_chunk > 0) {
+        const int64_t block_bytes = (int64_t)sg.max_block_words * 4;
+        const int64_t room = STAGED_LDS_LIMIT - block_bytes;                  // bytes left for the cells
+        const int64_t max_slice = room > 0 ? room / ((int64_t)sg.max_chunk_cells * W) : 0;   // vectors per cell that fit
         if (max_slice >= 1) {
             int32_t sv;
             if (opts && opts->slice_vectors) {
                 sv = opts->slice_vectors;
             } else {
-                // Latency bound either way: one vector per cell while at most 64 workgroups result, longer
-                // slices beyond (measured: 16-byte pieces of a 128-byte line shared by many workgroups on
-                // different XCDs cost more than the parallelism gains).
-                sv = pow2_at_least((plan->vecs_per_chunk + 63) / 64);
+                // Measured best over the size sweep: single-wavefront workgroups (no barriers at all) that move
+                // four vectors per lane, i.e. slices of up to 16 vectors, shortened while that leaves compute
+                // units without a work item.
+                sv = 16;
+                while (sv > 1 && ((int64_t)G * ((plan->vecs_per_chunk + sv - 1) / sv) < want || sv / 2 >= plan->vecs_per_chunk)) sv >>= 1;
                 while (sv > 1 && sv > max_slice) sv >>= 1;
             }
             if (sv <= max_slice) {
                 sg.available = true;
                 sg.log_slice_vectors = log2_of(sv);
-                sg.num_slices = (plan->vecs_per_chunk + sv - 1) / sv;
-                sg.lds_bytes = (int32_t)(table_bytes + (int64_t)sg.n_cells * sv * W);
-                // one lane per vector of the widest phase (loading, the widest level, storing), up to 1024
-                const int64_t widest = (int64_t)std::max(std::max(sg.n_in, sg.n_out), sg.max_level_tasks) * sv;
-                int32_t th = (opts && opts->staged_threads) ? opts->staged_threads
-                                                            : std::min(1024, std::max(64, pow2_at_least(widest)));
+                sg.slices_per_chunk = (plan->vecs_per_chunk + sv - 1) / sv;
+                sg.num_slices = (int64_t)G * sg.slices_per_chunk;
+                sg.lds_bytes = (int32_t)(block_bytes + (int64_t)sg.max_chunk_cells * sv * W);
+                int32_t th = (opts && opts->staged_threads) ? opts->staged_threads : 64;
                 sg.threads = th;
             }
         }

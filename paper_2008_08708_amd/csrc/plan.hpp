@@ -20,34 +20,37 @@ constexpr int32_t OPERAND_RANK_BITS = 8;
 constexpr int32_t OPERAND_RANK_MASK = (1 << OPERAND_RANK_BITS) - 1;
 constexpr int32_t MAX_SLOTS = 1 << (31 - OPERAND_RANK_BITS);
 
-// Tables of the staged lowering.  A *cell* is one (rank, chunk position) pair some send touches; the cells
-// a send reads before any send writes them come first (they are what a workgroup loads).  A *task* is
-// one cell write: a copy group with k destinations is k tasks, a reduce group is one.  Tasks are sorted
-// by dependency level: a group's level is one more than the highest level among the groups whose cells
-// it reads after they wrote them, or writes after they read or wrote them, so that the tasks of one level
-// touch no cell in conflicting ways and a workgroup barrier between levels is all the ordering needed.
-//   table words:  [0, n_cells)                       operand word (rank | position << 8) of every cell
-//                 [off_out,  off_out + 2 n_out)      the cells to store at the end: id, operand word
-//                 [off_lev,  off_lev + n_levels + 2) first task of every level, the end, the end again
-//                 [off_task, off_task + 2 n_tasks)   per task: destination cell | k << 16 ; k == 0: the
-//                                                    source cell of a copy, else the index (relative to
-//                                                    off_srcs) of the first of k source cells
-//                 [off_srcs, ...)                    source cells of the reduce tasks, in schedule order,
-//                                                    then three words of padding
-constexpr int32_t STAGED_MAX_CELLS = 1 << 16;
+// Tables of the staged lowering, one block per chunk (chunks never share memory, so each has its own cells,
+// levels and tasks).  A *cell* is one (rank, chunk position) pair some send of the chunk touches; the cells a send
+// reads before any send writes them come first (they are what a workgroup loads).  A *task* is one cell write:
+// a copy group with k destinations is k tasks, a reduce group is one.  Tasks are sorted by dependency level: a
+// group's level is one more than the highest level among the earlier groups whose cells it reads after they
+// wrote them, or writes after they read or wrote them, so the tasks of one level touch no cell in conflicting
+// ways and a workgroup barrier between levels is all the ordering needed.
+//   table:  G headers of STAGED_HEADER_WORDS words, then the blocks.
+//   header: block offset (words) | cells | loaded cells | stored cells | levels | tasks | sources | block words
+//   block:  [0, cells)                   operand word (rank | position << 8) of every cell
+//           then 2 x stored cells        the cells to store at the end: id, operand word
+//           then levels + 2              first task of every level, the end, the end again
+//           then 2 x tasks               per task: destination cell | k << 16 ; k == 0: the source cell of a copy,
+//                                        else the index of the first of k source cells in the list that follows
+//           then sources + 3             source cells of the reduce tasks, in schedule order, and padding
+constexpr int32_t STAGED_HEADER_WORDS = 8;
 constexpr int32_t STAGED_MAX_LEVELS = 256;                // a wavefront keeps the level table in four registers per lane
 constexpr int64_t STAGED_LDS_LIMIT = 160 * 1024;          // local data share of one gfx950 compute unit
-constexpr int64_t STAGED_AUTO_TOTAL_BYTES = 512ll << 10;  // measured crossover with the through-memory kernel
+constexpr int64_t STAGED_AUTO_TOTAL_BYTES = 16ll << 20;   // measured crossover with the through-memory kernel
 
 struct sccl_staged {
     bool available = false;
+    // totals over the chunks (statistics) and maxima over the chunks (sizes a workgroup needs)
     int32_t n_cells = 0, n_in = 0, n_out = 0, n_levels = 0, n_tasks = 0, max_level_tasks = 0;
-    int32_t off_out = 0, off_lev = 0, off_task = 0, off_srcs = 0;
+    int32_t max_chunk_cells = 0, max_chunk_in = 0, max_chunk_out = 0, max_block_words = 0;
     std::vector<int32_t> table;
     // launch shape
     int32_t log_slice_vectors = 0;
     int32_t threads = 0;
-    int64_t num_slices = 0;
+    int64_t slices_per_chunk = 0;
+    int64_t num_slices = 0;                               // work items: G x slices per chunk
     int32_t lds_bytes = 0;
     int32_t grid = 0;
 };

@@ -1,4 +1,4 @@
-"""GPU parity of the staged lowering (schedule run in the local data share): launch shapes, slice sizes,
+"""GPU parity of the staged lowering (a chunk's sends run in the local data share): launch shapes, slice sizes,
 ragged last slices, every vector width, several slices per workgroup, slot maps.  The other GPU tests already run
 every case under both lowerings (gpu_util.run_both); these pin what is specific to this one."""
 import numpy as np
@@ -53,7 +53,7 @@ def test_every_vector_width(epc, dtype):
 def test_one_workgroup_walks_every_slice(grid):
     topo = tp.torus2d(4, 4)
     coll, sched, _ = case(topo, 4, "allreduce")
-    epc = 4 * 21 + 4                                      # 22 vectors per chunk: 11 slices of 2, or 22 of 1
+    epc = 4 * 21 + 4                                      # 22 vectors per chunk: 11 slices of 2, or 22 of 1, per chunk
     bufs = host_inputs("uniform", "f32", 97, 16, coll.num_chunks, epc)
     for sv in (1, 2):
         want, got = run_both(topo, coll, sched, "f32", bufs, epc, label=f"staged-grid{grid}",
@@ -76,13 +76,13 @@ def test_config5_smallest_sizes_are_staged_by_default():
 
 
 def test_large_slices_use_the_whole_local_data_share():
-    # 64 cells x 128 vectors x 16 B = 128 KiB of cells: more than the 64 KiB a kernel gets without asking
+    # 8 cells per chunk x 1024 vectors x 16 B = 128 KiB of cells: more than the 64 KiB a kernel gets without asking
     topo = tp.hcm8()
     coll, sched, _ = case(topo, 1, "allreduce")
-    epc = 4 * (3 * 128 + 17)
+    epc = 4 * (3 * 1024 + 17)
     bufs = host_inputs("uniform", "f32", 103, 8, coll.num_chunks, epc)
     want, got = run_both(topo, coll, sched, "f32", bufs, epc, label="staged-128KiB",
-                         options={"lowering": STAGED, "slice_vectors": 128})
+                         options={"lowering": STAGED, "slice_vectors": 1024})
     assert_same_bits(want, got)
     for g in got[1:]:
         assert (bits(g) == bits(got[0])).all()

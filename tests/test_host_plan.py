@@ -306,17 +306,22 @@ def test_staged_lowering_choice_and_limits():
     assert st["num_cells"] == 16 * 64 and st["num_cells_loaded"] == 64 and st["num_cells_stored"] == 15 * 64
     _, st2 = plan_status(topo, arc, ar, "f32", 4)
     assert st2["num_cells_loaded"] == 16 * 64 and st2["num_levels"] == 2 * st["num_levels"]
-    # auto: staged up to 512 KiB over all ranks, through memory above
-    for epc, want in ((1 << 7, sccl.SCCL_LOWER_STAGED), (1 << 8, sccl.SCCL_LOWER_MEMORY)):
+    # auto: staged up to 16 MiB over all ranks, through memory above
+    for epc, want in ((1 << 12, sccl.SCCL_LOWER_STAGED), (1 << 13, sccl.SCCL_LOWER_MEMORY)):
         _, st = plan_status(topo, arc, ar, "f32", epc)
         assert P_bytes(st) == 16 * 64 * epc * 4 and st["lowering"] == want
     # explicit choices
-    assert plan_status(topo, arc, ar, "f32", 1 << 14, options={"lowering": sccl.SCCL_LOWER_STAGED})[1]["lowering"] == sccl.SCCL_LOWER_STAGED
+    st = plan_status(topo, arc, ar, "f32", 1 << 14, options={"lowering": sccl.SCCL_LOWER_STAGED})[1]
+    assert st["lowering"] == sccl.SCCL_LOWER_STAGED and st["slice_vectors"] == 16 and st["staged_threads"] == 64
+    st = plan_status(topo, arc, ar, "f32", 16)[1]          # 4 vectors per chunk, 64 chunks: one vector per work item
+    assert st["slice_vectors"] == 1 and st["num_slices"] == 256
     assert plan_status(topo, arc, ar, "f32", 4, options={"lowering": sccl.SCCL_LOWER_MEMORY})[1]["lowering"] == sccl.SCCL_LOWER_MEMORY
-    # a slice of every cell must fit 160 KiB together with the tables: 1024 cells x 16 vectors x 16 B is too much
-    assert plan_status(topo, arc, ar, "f32", 1 << 10, options={"lowering": sccl.SCCL_LOWER_STAGED, "slice_vectors": 16})[0] == "SCCL_ERR_INVALID_ARG"
+    # a slice of every cell of a chunk (16 ranks hold it) must fit 160 KiB together with the chunk's tables
+    assert plan_status(topo, arc, ar, "f32", 1 << 12, options={"lowering": sccl.SCCL_LOWER_STAGED, "slice_vectors": 1024})[0] == "SCCL_ERR_INVALID_ARG"
+    _, st = plan_status(topo, arc, ar, "f32", 1 << 12, options={"lowering": sccl.SCCL_LOWER_STAGED, "slice_vectors": 512})
+    assert st["slice_vectors"] == 512 and st["num_slices"] == 64 * 2 and 128 * 1024 < st["staged_lds_bytes"] <= 160 * 1024
     _, st = plan_status(topo, arc, ar, "f32", 1 << 10, options={"lowering": sccl.SCCL_LOWER_STAGED, "slice_vectors": 4})
-    assert st["slice_vectors"] == 4 and st["num_slices"] == 64 and st["staged_lds_bytes"] <= 160 * 1024
+    assert st["slice_vectors"] == 4 and st["num_slices"] == 64 * 64
     for bad in ({"lowering": 3}, {"slice_vectors": 3}, {"staged_threads": 96}, {"reserved": 1}):
         assert plan_status(topo, arc, ar, "f32", 4, options=bad)[0] == "SCCL_ERR_INVALID_ARG"
 
