@@ -346,7 +346,9 @@ struct StagedArgs {
     int64_t vecs_per_chunk;
     int64_t slices_per_chunk;
     int32_t log_slice;            // vectors per slice = 1 << log_slice
-    int32_t block_words;          // room for the largest chunk block, in words (a multiple of 4)
+    int32_t block_words;          // stride of the chunk blocks, in words (a multiple of 4)
+    int32_t cell_words_room;      // words reserved for cell words in every block
+    int32_t pad;
     char* bufs[SCCL_MAX_RANKS];
 };
 
@@ -357,25 +359,21 @@ __device__ __forceinline__ char* rank_base(uint32_t lo, uint32_t hi, int32_t ran
 }
 
 // Offsets of the parts of one chunk's block inside the local copy, and their sizes.
-struct StagedBlock { int32_t n_in, n_out, n_levels, off_out, off_lev, off_task, off_srcs, max_level; };
+struct StagedBlock { int32_t n_in, n_out, n_levels, off_out, off_lev, off_task, off_extra; };
 
-// One task as a lane holds it: the two table words (t0 < 0: no task) and, for a reduce task, its
-// first four source cells.
+// One task record as a lane holds it (t0 < 0: no task).
 struct StagedTask { int32_t t0, t1, s[4]; };
 
-__device__ __forceinline__ void fetch_words(StagedTask& t, const int32_t* tab, const StagedBlock& b,
-                                            int32_t t_lo, int32_t t_hi, int32_t i, int32_t ls) {
+__device__ __forceinline__ void fetch_task(StagedTask& t, const int32_t* tab, const StagedBlock& b,
+                                           int32_t t_lo, int32_t t_hi, int32_t i, int32_t ls) {
     const int32_t task = t_lo + (i >> ls);
-    t.t0 = -1; t.t1 = 0;
+    t.t0 = -1;
     if (task < t_hi) {
-        t.t0 = tab[b.off_task + 2 * task];
-        t.t1 = tab[b.off_task + 2 * task + 1];
-    }
-}
-__device__ __forceinline__ void fetch_sources(StagedTask& t, const int32_t* tab, const StagedBlock& b) {
-    if (t.t0 >= (1 << 16)) {                                       // a reduce task; the list is padded by three words
-#pragma unroll
-        for (int j = 0; j < 4; j++) t.s[j] = tab[b.off_srcs + t.t1 + j];
+        const u32x4* rec = (const u32x4*)(tab + b.off_task + STAGED_TASK_WORDS * task);   // 16-byte aligned
+        const u32x4 lo = rec[0];
+        const u32x2 hi = *(const u32x2*)(rec + 1);
+        t.t0 = (int32_t)lo.x; t.t1 = (int32_t)lo.y; t.s[0] = (int32_t)lo.z; t.s[1] = (int32_t)lo.w;
+        t.s[2] = (int32_t)hi.x; t.s[3] = (int32_t)hi.y;
     }
 }
 
@@ -400,7 +398,7 @@ __device__ __forceinline__ void run_task(typename VecOf<W>::type* cells, const i
 #pragma unroll
     for (int j = 0; j < 4; j++)
         if (j < k) acc.add(x[j]);
-    for (int32_t j = 4; j < k; j++) acc.add(cells[(tab[b.off_srcs + t.t1 + j] << ls) + v]);
+    for (int32_t j = 4; j < k; j++) acc.add(cells[(tab[b.off_extra + t.t1 + j - 4] << ls) + v]);
     cells[(dst << ls) + v] = acc.template done<V>();
 }
 
@@ -445,27 +443,35 @@ __global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
         const int64_t slice_off = v0 * W;
         const bool live = (tid & vmask) < here;                    // this lane's vector exists in this slice
 
-        // the chunk's header (the same in every lane) and its block
-        table_ptr h = gt + (int64_t)c * STAGED_HEADER_WORDS;
-        const int32_t blk = h[0], n_cells = h[1], n_tasks = h[5], words = h[7];
+        // Everything this item needs first is fetched in ONE round trip, because where it sits does not depend
+        // on the header: the header itself (scalar), the level table into registers, the operand words of the
+        // cells to load, and the whole block into the local data share.
+        const int32_t* gblock = a.table + (int64_t)c * a.block_words;
+        table_ptr h = (table_ptr)gblock;
+        const int32_t n_cells = h[0], n_tasks = h[4];
         StagedBlock b;
-        b.n_in = h[2]; b.n_out = h[3]; b.n_levels = h[4];
-        b.off_out = n_cells;
-        b.off_lev = b.off_out + 2 * b.n_out;
-        b.off_task = b.off_lev + b.n_levels + 2;
-        b.off_srcs = b.off_task + 2 * n_tasks;
-        const int32_t* gblock = a.table + blk;
-        // the level table (at most 256 entries) goes to registers, so that level bounds cost no memory access
-        int32_t levreg[4];
+        b.n_in = h[1]; b.n_out = h[2]; b.n_levels = h[3];
+        b.off_lev = STAGED_HEADER_WORDS + a.cell_words_room;
+        b.off_out = b.off_lev + b.n_levels + 2;
+        b.off_task = (b.off_out + 2 * b.n_out + 3) & ~3;
+        b.off_extra = b.off_task + STAGED_TASK_WORDS * n_tasks;
+        (void)n_cells;
+        int32_t levreg[4];                                         // entries past the table are never used
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-            const int32_t l = (tid & 63) + 64 * q;
-            levreg[q] = gblock[b.off_lev + (l < b.n_levels ? l : b.n_levels)];
+            const int32_t l = STAGED_HEADER_WORDS + a.cell_words_room + (tid & 63) + 64 * q;
+            levreg[q] = l < a.block_words ? gblock[l] : 0;
+        }
+        int32_t w0[UA];                                            // operand words of the first cells this lane loads
+#pragma unroll
+        for (int u = 0; u < UA; u++) {
+            const int32_t i = u * BT + tid;
+            w0[u] = (i >> ls) < a.cell_words_room ? gblock[STAGED_HEADER_WORDS + (i >> ls)] : 0;
         }
         {   // the block goes to the local data share, 16 bytes per lane and trip
             const u32x4* src = (const u32x4*)gblock;
             u32x4* dst = (u32x4*)staged_lds;
-            for (int32_t i = tid; i < words / 4; i += BT) dst[i] = src[i];
+            for (int32_t i = tid; i < a.block_words / 4; i += BT) dst[i] = src[i];
         }
 
         // ---- (1) load: cell i < n_in is the i-th loaded cell; its operand word comes straight from memory
@@ -475,8 +481,12 @@ __global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
 #pragma unroll
             for (int u = 0; u < UA; u++) {
                 const int32_t i = base + u * BT + tid;
+                w[u] = base == 0 ? w0[u] : ((i >> ls) < a.cell_words_room ? gblock[STAGED_HEADER_WORDS + (i >> ls)] : 0);
+            }
+#pragma unroll
+            for (int u = 0; u < UA; u++) {
+                const int32_t i = base + u * BT + tid;
                 ok[u] = i < in_lanes && (i & vmask) < here;
-                w[u] = ok[u] ? gblock[i >> ls] : 0;
             }
 #pragma unroll
             for (int u = 0; u < UA; u++) {
@@ -493,28 +503,25 @@ __global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
         }
         staged_sync(one_wave);
 
-        // ---- (2) the schedule, level by level.  The block is read-only, so a lane fetches its task of the
-        // NEXT level (two words, then a reduce task's sources) while the cells of the current level are on
-        // their way.  The first cell this lane stores in phase 3, (cell id, operand word), is fetched here too.
+        // ---- (2) the schedule, level by level.  The block is read-only, so a lane fetches its task record of
+        // the NEXT level together with the cells of the current one: one local-memory round trip per level.
+        // The first cell this lane stores in phase 3, (cell id, operand word), is fetched here too.
         const bool ok0 = tid < out_lanes && live;
         const int32_t out_c0 = ok0 ? tab[b.off_out + 2 * (tid >> ls)] : 0;
         const int32_t out_w0 = ok0 ? tab[b.off_out + 2 * (tid >> ls) + 1] : 0;
         int32_t lo0 = level_first(levreg, 0, b.n_levels), lo1 = level_first(levreg, 1, b.n_levels);
         StagedTask cur;
-        fetch_words(cur, tab, b, lo0, lo1, tid, ls);
-        fetch_sources(cur, tab, b);
+        fetch_task(cur, tab, b, lo0, lo1, tid, ls);
         for (int32_t lv = 0; lv < b.n_levels; lv++) {
             const int32_t lo2 = level_first(levreg, lv + 2, b.n_levels);
             StagedTask nxt;
-            fetch_words(nxt, tab, b, lo1, lo2, tid, ls);
+            fetch_task(nxt, tab, b, lo1, lo2, tid, ls);
             if (live) run_task<DT, W>(cells, tab, b, cur, tid & vmask, ls);
-            fetch_sources(nxt, tab, b);
             const int32_t lanes = (lo1 - lo0) << ls;
             for (int32_t i = tid + BT; i < lanes; i += BT) {       // levels wider than the workgroup
                 if ((i & vmask) >= here) continue;
                 StagedTask t;
-                fetch_words(t, tab, b, lo0, lo1, i, ls);
-                fetch_sources(t, tab, b);
+                fetch_task(t, tab, b, lo0, lo1, i, ls);
                 run_task<DT, W>(cells, tab, b, t, i & vmask, ls);
             }
             cur = nxt;
@@ -759,6 +766,7 @@ static sccl_status_t launch_staged(const sccl_plan_t* plan, void* const* rank_bu
     args.slices_per_chunk = sg.slices_per_chunk;
     args.log_slice = sg.log_slice_vectors;
     args.block_words = sg.max_block_words;
+    args.cell_words_room = sg.cell_words_room;
     for (int32_t n = 0; n < plan->P; n++) args.bufs[n] = (char*)rank_buffers[n];
     staged_fn fn = pick_staged_kernel(plan->dtype, plan->vector_bytes);
     hipLaunchKernelGGL(fn, dim3((unsigned)sg.grid), dim3((unsigned)sg.threads), (size_t)sg.lds_bytes, (hipStream_t)stream, args);

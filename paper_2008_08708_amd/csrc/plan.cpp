@@ -34,7 +34,8 @@ bool build_staged_tables(const sccl_plan& plan, sccl_staged* out) {
     sccl_staged& sg = *out;
     sg = sccl_staged();
     const int32_t G = plan.G;
-    std::vector<int32_t> header((size_t)G * STAGED_HEADER_WORDS, 0), blocks;
+    struct Pieces { std::vector<int32_t> cell_word, out_cells, lev_first, tasks, extra; int32_t n_in = 0, n_levels = 0; };
+    std::vector<Pieces> pieces((size_t)G);
     for (int32_t c = 0; c < G; c++) {
         // the chunk's groups: (pointer to header word) in step order
         std::vector<const int32_t*> groups;
@@ -96,58 +97,78 @@ bool build_staged_tables(const sccl_plan& plan, sccl_staged* out) {
         }
         if (n_levels >= STAGED_MAX_LEVELS) return false;
 
-        // pass 3: the tasks, level by level, groups in step order inside a level
-        std::vector<int32_t> out_cells, lev_first((size_t)n_levels + 1, 0), tasks, srcs;
+        // pass 3: the tasks, level by level, groups in step order inside a level.  A task record is eight
+        // words: destination cell | k << 16, then for a copy (k == 0) the source cell, for a reduce the index
+        // of its fifth source in the overflow list, then the first four sources, then padding.
+        std::vector<int32_t> out_cells, lev_first((size_t)n_levels + 1, 0), tasks, extra;
         for (int32_t i = 0; i < n_cells; i++)
             if (written[(size_t)i]) { out_cells.push_back(i); out_cells.push_back(cell_word[(size_t)i]); }
         int32_t widest = 0;
         for (int32_t lv = 1; lv <= n_levels; lv++) {
-            lev_first[(size_t)lv - 1] = (int32_t)(tasks.size() / 2);
+            lev_first[(size_t)lv - 1] = (int32_t)(tasks.size() / STAGED_TASK_WORDS);
             for (size_t g = 0; g < n_groups; g++) {
                 if (level[g] != lv) continue;
                 const int32_t* op = groups[g];
                 const int32_t k = op[0] >> 8;
                 if (op[0] & OP_KIND_REDUCE) {
-                    tasks.push_back(cell[op[1]] | (k << 16));
-                    tasks.push_back((int32_t)srcs.size());
-                    for (int32_t j = 0; j < k; j++) srcs.push_back(cell[op[2 + j]]);
+                    int32_t rec[STAGED_TASK_WORDS] = {cell[op[1]] | (k << 16), (int32_t)extra.size(), 0, 0, 0, 0, 0, 0};
+                    for (int32_t j = 0; j < k; j++) {
+                        if (j < 4) rec[2 + j] = cell[op[2 + j]];
+                        else extra.push_back(cell[op[2 + j]]);
+                    }
+                    tasks.insert(tasks.end(), rec, rec + STAGED_TASK_WORDS);
                 } else {
-                    for (int32_t j = 0; j < k; j++) { tasks.push_back(cell[op[2 + j]]); tasks.push_back(cell[op[1]]); }
+                    for (int32_t j = 0; j < k; j++) {
+                        const int32_t rec[STAGED_TASK_WORDS] = {cell[op[2 + j]], cell[op[1]], 0, 0, 0, 0, 0, 0};
+                        tasks.insert(tasks.end(), rec, rec + STAGED_TASK_WORDS);
+                    }
                 }
             }
-            widest = std::max(widest, (int32_t)(tasks.size() / 2) - lev_first[(size_t)lv - 1]);
+            widest = std::max(widest, (int32_t)(tasks.size() / STAGED_TASK_WORDS) - lev_first[(size_t)lv - 1]);
         }
-        lev_first[(size_t)n_levels] = (int32_t)(tasks.size() / 2);
+        lev_first[(size_t)n_levels] = (int32_t)(tasks.size() / STAGED_TASK_WORDS);
         lev_first.push_back(lev_first.back());            // the kernel reads one level ahead
-        const int32_t n_srcs = (int32_t)srcs.size();
-        srcs.insert(srcs.end(), 3, 0);                    // and four sources at a time
 
-        // the block: cell words | stored cells | level table | tasks | sources, padded to whole 16-byte vectors
-        int32_t* h = &header[(size_t)c * STAGED_HEADER_WORDS];
-        h[0] = (int32_t)blocks.size();                    // relative to the end of the headers; fixed up below
-        h[1] = n_cells; h[2] = n_in; h[3] = (int32_t)(out_cells.size() / 2); h[4] = n_levels;
-        h[5] = (int32_t)(tasks.size() / 2); h[6] = n_srcs;
-        const size_t before = blocks.size();
-        blocks.insert(blocks.end(), cell_word.begin(), cell_word.end());
-        blocks.insert(blocks.end(), out_cells.begin(), out_cells.end());
-        blocks.insert(blocks.end(), lev_first.begin(), lev_first.end());
-        blocks.insert(blocks.end(), tasks.begin(), tasks.end());
-        blocks.insert(blocks.end(), srcs.begin(), srcs.end());
-        while (blocks.size() % 4) blocks.push_back(0);
-        h[7] = (int32_t)(blocks.size() - before);
+        const int32_t n_out = (int32_t)(out_cells.size() / 2), n_tasks = (int32_t)(tasks.size() / STAGED_TASK_WORDS);
+        Pieces& pc = pieces[(size_t)c];
+        pc.cell_word = cell_word; pc.out_cells = out_cells; pc.lev_first = lev_first; pc.tasks = tasks; pc.extra = extra;
+        pc.n_in = n_in; pc.n_levels = n_levels;
 
-        sg.n_cells += n_cells; sg.n_in += n_in; sg.n_out += h[3]; sg.n_tasks += h[5];
+        sg.n_cells += n_cells; sg.n_in += n_in; sg.n_out += n_out; sg.n_tasks += n_tasks;
         sg.n_levels = std::max(sg.n_levels, n_levels);
         sg.max_level_tasks = std::max(sg.max_level_tasks, widest);
         sg.max_chunk_cells = std::max(sg.max_chunk_cells, n_cells);
         sg.max_chunk_in = std::max(sg.max_chunk_in, n_in);
-        sg.max_chunk_out = std::max(sg.max_chunk_out, h[3]);
-        sg.max_block_words = std::max(sg.max_block_words, h[7]);
+        sg.max_chunk_out = std::max(sg.max_chunk_out, n_out);
     }
-    const int32_t base = (int32_t)header.size();         // G * 8 words: a multiple of 4
-    for (int32_t c = 0; c < G; c++) header[(size_t)c * STAGED_HEADER_WORDS] += base;
-    sg.table = header;
-    sg.table.insert(sg.table.end(), blocks.begin(), blocks.end());
+    // The blocks, all of one stride, so that a workgroup can fetch everything it needs first (header, cell words,
+    // level table) without knowing the header: header | cell words, room for the most any chunk has | stored
+    // cells | level table | (pad) task records | overflow sources | (pad).
+    sg.cell_words_room = (sg.max_chunk_cells + 3) & ~3;
+    auto emit = [&](const Pieces& pc, std::vector<int32_t>& o) {
+        const size_t before = o.size();
+        const int32_t hdr[STAGED_HEADER_WORDS] = {(int32_t)pc.cell_word.size(), pc.n_in, (int32_t)(pc.out_cells.size() / 2), pc.n_levels,
+                                                  (int32_t)(pc.tasks.size() / STAGED_TASK_WORDS), (int32_t)pc.extra.size(), 0, 0};
+        o.insert(o.end(), hdr, hdr + STAGED_HEADER_WORDS);
+        o.insert(o.end(), pc.cell_word.begin(), pc.cell_word.end());
+        o.resize(before + STAGED_HEADER_WORDS + (size_t)sg.cell_words_room, 0);
+        o.insert(o.end(), pc.lev_first.begin(), pc.lev_first.end());
+        o.insert(o.end(), pc.out_cells.begin(), pc.out_cells.end());
+        while ((o.size() - before) % 4) o.push_back(0);               // records are read as 16-byte vectors
+        o.insert(o.end(), pc.tasks.begin(), pc.tasks.end());
+        o.insert(o.end(), pc.extra.begin(), pc.extra.end());
+        while ((o.size() - before) % 4) o.push_back(0);
+        return (int32_t)(o.size() - before);
+    };
+    for (const Pieces& pc : pieces) {
+        std::vector<int32_t> scratch;
+        sg.max_block_words = std::max(sg.max_block_words, emit(pc, scratch));
+    }
+    sg.table.clear();
+    for (int32_t c = 0; c < G; c++) {
+        emit(pieces[(size_t)c], sg.table);
+        sg.table.resize((size_t)(c + 1) * sg.max_block_words, 0);
+    }
     return true;
 }
 

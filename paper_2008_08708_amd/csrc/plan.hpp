@@ -27,15 +27,19 @@ constexpr int32_t MAX_SLOTS = 1 << (31 - OPERAND_RANK_BITS);
 // group's level is one more than the highest level among the earlier groups whose cells it reads after they
 // wrote them, or writes after they read or wrote them, so the tasks of one level touch no cell in conflicting
 // ways and a workgroup barrier between levels is all the ordering needed.
-//   table:  G headers of STAGED_HEADER_WORDS words, then the blocks.
-//   header: block offset (words) | cells | loaded cells | stored cells | levels | tasks | sources | block words
-//   block:  [0, cells)                   operand word (rank | position << 8) of every cell
-//           then 2 x stored cells        the cells to store at the end: id, operand word
-//           then levels + 2              first task of every level, the end, the end again
-//           then 2 x tasks               per task: destination cell | k << 16 ; k == 0: the source cell of a copy,
-//                                        else the index of the first of k source cells in the list that follows
-//           then sources + 3             source cells of the reduce tasks, in schedule order, and padding
+//   table:  G blocks of one stride (the largest block), so that a workgroup can fetch what it needs first
+//           (header, cell words, level table) before it knows the header.
+//   block:  8 header words        cells | loaded cells | stored cells | levels | tasks | overflow sources | 0 | 0
+//           cell words            operand word (rank | position << 8) of every cell; room for the most cells any
+//                                 chunk has, rounded up to 4
+//           levels + 2            first task of every level, the end, the end again
+//           2 x stored cells      the cells to store at the end: id, operand word; then padding to 4 words
+//           8 x tasks             per task: destination cell | k << 16 ; k == 0: the source cell of a copy,
+//                                 else the index of the task's fifth source in the overflow list ; the
+//                                 first four source cells in schedule order ; two words of padding
+//           overflow sources      fifth and later sources of reduce tasks with more than four; padding
 constexpr int32_t STAGED_HEADER_WORDS = 8;
+constexpr int32_t STAGED_TASK_WORDS = 8;
 constexpr int32_t STAGED_MAX_LEVELS = 256;                // a wavefront keeps the level table in four registers per lane
 constexpr int64_t STAGED_LDS_LIMIT = 160 * 1024;          // local data share of one gfx950 compute unit
 constexpr int64_t STAGED_AUTO_TOTAL_BYTES = 16ll << 20;   // measured crossover with the through-memory kernel
@@ -44,7 +48,7 @@ struct sccl_staged {
     bool available = false;
     // totals over the chunks (statistics) and maxima over the chunks (sizes a workgroup needs)
     int32_t n_cells = 0, n_in = 0, n_out = 0, n_levels = 0, n_tasks = 0, max_level_tasks = 0;
-    int32_t max_chunk_cells = 0, max_chunk_in = 0, max_chunk_out = 0, max_block_words = 0;
+    int32_t max_chunk_cells = 0, max_chunk_in = 0, max_chunk_out = 0, max_block_words = 0, cell_words_room = 0;
     std::vector<int32_t> table;
     // launch shape
     int32_t log_slice_vectors = 0;
