@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # what the same counter reads for the 1 GiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  Keyed by
 # (workload, grid, block_threads, vectors_per_thread); the figures and commands are in profiles/.
 MEASURED_TRAFFIC = {
-    ("cfg3", 256, 256, 4): (2 * 1095450.0 + 2664775.8) * 1024,
+    ("cfg3", 256, 256, 4): (2 * 1097471.0 + 2658935.8) * 1024,
     ("cfg4", 256, 256, 8): (2 * 2542746.1 + 7158514.2) * 1024,
     ("cfg2", 256, 256, 8): (2 * 124550.7 + 458752.0) * 1024,
 }

@@ -126,6 +126,19 @@ def test_sixty_four_ranks():
     assert_same_bits(want, got)
 
 
+def test_sixty_four_ranks_fan_in_sixty_three():
+    # K64: every reduce group has 63 sources (batches of four in one kernel, an overflow list in the other)
+    topo = tp.complete(64)
+    sched, coll = allreduce_of(topo, 1)
+    assert sched.num_steps == 2
+    for dtype, dist, epc in (("f32", "uniform", 4 * 5 + 4), ("f16", "normal", 8 * 3)):
+        bufs = host_inputs(dist, dtype, 41, 64, coll.num_chunks, epc)
+        want, got = run_both(topo, coll, sched, dtype, bufs, epc, label=f"K64-{dtype}")
+        assert_same_bits(want, got)
+        for g in got[1:]:
+            assert (bits(g) == bits(got[0])).all()
+
+
 def test_addition_order_inside_a_group_is_the_schedules():
     t = tp.complete(4)
     ar = col.allreduce(4, 1)
