@@ -340,7 +340,7 @@ __global__ void __launch_bounds__(256) copy16_kernel(u32x4* __restrict__ dst, co
 // schedule, so the bits equal the other lowerings'.  A chunk's chain of sends costs local-memory latency
 // per level instead of a cache round trip per group, which is what small buffers are bound by.
 struct StagedArgs {
-    const int32_t* table;         // per-chunk headers and blocks, see plan.hpp
+    const int32_t* table;         // one block per chunk, see plan.hpp
     int64_t chunk_bytes;
     int64_t num_items;            // chunks x slices per chunk
     int64_t vecs_per_chunk;
@@ -427,7 +427,6 @@ __global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
     const int32_t tid = (int32_t)threadIdx.x, BT = (int32_t)blockDim.x;
     const bool one_wave = BT <= 64;
     const int32_t ls = a.log_slice, sv = 1 << ls, vmask = sv - 1;
-    table_ptr gt = (table_ptr)a.table;                             // scalar loads of the header
 
     // lane n of every wavefront keeps the base pointer of rank n (P <= 64 = lanes of a wavefront)
     const uint64_t mine = (uint64_t)a.bufs[tid & 63];
@@ -448,14 +447,13 @@ __global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
         // cells to load, and the whole block into the local data share.
         const int32_t* gblock = a.table + (int64_t)c * a.block_words;
         table_ptr h = (table_ptr)gblock;
-        const int32_t n_cells = h[0], n_tasks = h[4];
+        const int32_t n_tasks = h[4];
         StagedBlock b;
         b.n_in = h[1]; b.n_out = h[2]; b.n_levels = h[3];
         b.off_lev = STAGED_HEADER_WORDS + a.cell_words_room;
         b.off_out = b.off_lev + b.n_levels + 2;
         b.off_task = (b.off_out + 2 * b.n_out + 3) & ~3;
         b.off_extra = b.off_task + STAGED_TASK_WORDS * n_tasks;
-        (void)n_cells;
         int32_t levreg[4];                                         // entries past the table are never used
 #pragma unroll
         for (int q = 0; q < 4; q++) {
