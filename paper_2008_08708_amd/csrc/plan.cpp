@@ -172,7 +172,6 @@ bool build_staged_tables(const sccl_plan& plan, sccl_staged* out) {
     return true;
 }
 
-int32_t pow2_at_least(int64_t x) { int32_t p = 1; while (p < x && p < (1 << 30)) p <<= 1; return p; }
 int32_t log2_of(int32_t p) { int32_t l = 0; while ((1 << l) < p) l++; return l; }
 
 }  // namespace
