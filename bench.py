@@ -152,13 +152,14 @@ def cpu_baseline(run, wl):
     sf, epc = run["sf"], run["epc"]
     sched = osched.Schedule(sf.rounds, sf.sends)
     threads = min(16, os.cpu_count() or 1, executor.max_threads())
+    layout = {} if sf.slot is None else {"slot": sf.slot, "slots_per_rank": sf.slots_per_rank}
     host_in = [p.cpu().numpy() for p in run["pristine"]]
     times = []
     host = None
     for rep in range(3):
         host = [h.copy() for h in host_in]
         t0 = time.perf_counter()
-        executor.execute(wl.dtype, sf.num_chunks, epc, sched, host, threads=threads)
+        executor.execute(wl.dtype, sf.num_chunks, epc, sched, host, threads=threads, **layout)
         times.append(time.perf_counter() - t0)
     # the GPU's result on the same inputs
     for w, p in zip(run["work"], run["pristine"]):
@@ -174,7 +175,7 @@ def cpu_baseline(run, wl):
     med = sorted(times)[1]
     host1 = [h.copy() for h in host_in]
     t0 = time.perf_counter()
-    executor.execute(wl.dtype, sf.num_chunks, epc, sched, host1, threads=1)
+    executor.execute(wl.dtype, sf.num_chunks, epc, sched, host1, threads=1, **layout)
     one = time.perf_counter() - t0
     return {"value": run["stats"]["bytes_min"] / med / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
             "value_one_core": run["stats"]["bytes_min"] / one / 1e9,
@@ -315,11 +316,19 @@ def main():
                 except ScclError:
                     stg_med = None
             graph_us = graph_us_per_execute(w) if w.bytes_per_rank <= (1 << 20) else None
+            oracle = None                                    # (GB/s on the host cores, GB/s on one core, cores, bitwise equal)
+            if s["num_nodes"] * w.bytes_per_rank <= (4 << 30):
+                kept = time_workload(w, 1, 0, keep=True)
+                base, same = cpu_baseline(kept, w)
+                oracle = (base["value"], base["value_one_core"], base["cores"], same)
+                sccl.sccl_plan_destroy(kept["plan"])
+                del kept
+                torch.cuda.empty_cache()
             step_med, _, _ = median_us(w, steps, "sccl_execute_stepwise")
             cpy_med = median_us(w, steps, "sccl_execute_memcpy")[0] if s["num_reduce_groups"] == 0 else None
             rows.append((label, s["num_nodes"], w.bytes_per_rank, s["chunk_bytes"], s["num_steps"], s["bytes_min"],
                          med, mn, s["bytes_min"] / (med * 1e-6) / 1e9, "staged" if s["lowering"] == SCCL_LOWER_STAGED else "memory",
-                         s["num_levels"], s["grid_workgroups"], mem_med, stg_med, step_med, cpy_med, graph_us))
+                         s["num_levels"], s["grid_workgroups"], mem_med, stg_med, step_med, cpy_med, graph_us, oracle))
             fmt = lambda x: "-" if x is None else format(x, ".1f")
             print(f"[report] {label}: default ({rows[-1][9]}) {med:.1f} us ({rows[-1][8]:.1f} GB/s), through memory {fmt(mem_med)} us, "
                   f"staged {fmt(stg_med)} us, per-step kernels {fmt(step_med)} us, per-send copies {fmt(cpy_med)} us, "
@@ -329,13 +338,16 @@ def main():
         with open(args.report, "w") as f:
             f.write("| workload | P | bytes/rank | chunk bytes | S | bytes_min | sccl_execute: median us | min us | effective GB/s | % of 8 TB/s "
                     "| lowering | levels | grid | through memory: us | staged: us | one kernel per step: us | one copy per send: us "
-                    "| each of 20 in one HIP graph: us |\n")
-            f.write("|" + "---|" * 18 + "\n")
+                    "| each of 20 in one HIP graph: us | oracle on the host cores: GB/s (cores) | oracle on one core: GB/s "
+                    "| full buffers bitwise equal to the oracle's |\n")
+            f.write("|" + "---|" * 21 + "\n")
             fmt = lambda x: "-" if x is None else format(x, ".1f")
             for r in rows:
                 f.write(f"| {r[0]} | {r[1]} | {r[2]} | {r[3]} | {r[4]} | {r[5]} | {r[6]:.1f} | {r[7]:.1f} | {r[8]:.1f} | "
                         f"{100 * r[8] / HBM_PEAK_GBS:.1f} | {r[9]} | {r[10]} | {r[11]} | {fmt(r[12])} | {fmt(r[13])} | "
-                        f"{fmt(r[14])} | {fmt(r[15])} | {fmt(r[16])} |\n")
+                        f"{fmt(r[14])} | {fmt(r[15])} | {fmt(r[16])} | "
+                        + ("- | - | (sampled windows: tests/test_gpu_fullsize.py) |\n" if r[17] is None else
+                           f"{r[17][0]:.1f} ({r[17][2]}) | {r[17][1]:.1f} | {'yes' if r[17][3] else 'NO'} |\n"))
         # ---- the paper's size-dependent choice between two algorithms (section 5.5) on this hardware: the
         # latency-optimal and the bandwidth-optimal torus algorithm at every size, the (alpha, beta) of the cost
         # model fitted to the measurements, and what the model would have chosen.
