@@ -186,7 +186,12 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
     if (P < 1 || P > SCCL_MAX_RANKS || G < 1 || S < 1) return SCCL_ERR_INVALID_ARG;
     if (!coll->pre || !coll->post || !sched->rounds) return SCCL_ERR_INVALID_ARG;
     if (coll->elems_per_chunk < 0) return SCCL_ERR_INVALID_ARG;
-    if (coll->dtype != SCCL_I32 && coll->dtype != SCCL_F32 && coll->dtype != SCCL_F16) return SCCL_ERR_INVALID_ARG;
+    // a caller may hand over any integer in the enum's place: look at the bits before treating it as the enum
+    int32_t dtype_bits;
+    static_assert(sizeof(coll->dtype) == sizeof(dtype_bits), "sccl_dtype_t is a 32-bit enum in this ABI");
+    std::memcpy(&dtype_bits, &coll->dtype, sizeof(dtype_bits));
+    if (dtype_bits != SCCL_I32 && dtype_bits != SCCL_F32 && dtype_bits != SCCL_F16) return SCCL_ERR_INVALID_ARG;
+    const sccl_dtype_t dtype = (sccl_dtype_t)dtype_bits;
     if (sched->num_sends < 0 || (sched->num_sends > 0 && !sched->sends)) return SCCL_ERR_INVALID_ARG;
     if (topo->num_bw < 0 || (topo->num_bw > 0 && !topo->bw)) return SCCL_ERR_INVALID_ARG;
     if (opts) {
@@ -405,12 +410,18 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
 
     // ---- record the problem and the statistics
     plan->P = P; plan->G = G; plan->S = S;
-    plan->dtype = coll->dtype;
+    plan->dtype = dtype;
     plan->combining = coll->combining;
     plan->elems_per_chunk = coll->elems_per_chunk;
     plan->rounds.assign(sched->rounds, sched->rounds + S);
     if (opts) plan->opts = *opts;
-    const int64_t chunk_bytes = coll->elems_per_chunk * elem_bytes(coll->dtype);
+    // sizes in bytes must fit 63 bits: the chunk, a rank buffer, and the two byte counts of the statistics
+    int64_t chunk_bytes, probe;
+    if (__builtin_mul_overflow(coll->elems_per_chunk, (int64_t)elem_bytes(dtype), &chunk_bytes) ||
+        __builtin_mul_overflow(chunk_bytes, (int64_t)slots, &probe) ||
+        __builtin_mul_overflow(chunk_bytes, chunks_min, &probe) ||
+        __builtin_mul_overflow(chunk_bytes, chunks_unfused, &probe))
+        return SCCL_ERR_INVALID_ARG;
     sccl_stats_t& st = plan->stats;
     st.num_nodes = P; st.num_global_chunks = G;
     st.num_steps = S; st.num_rounds = (int32_t)R; st.k = (int32_t)(R - S);
@@ -431,7 +442,7 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
 
     // ---- launch shape: how the element range of a chunk is cut into tiles (work distribution per chunk size)
     int32_t W = 16;
-    while (W > elem_bytes(coll->dtype) && chunk_bytes % W != 0) W >>= 1;
+    while (W > elem_bytes(dtype) && chunk_bytes % W != 0) W >>= 1;
     plan->vector_bytes = W;
     plan->vecs_per_chunk = chunk_bytes / W;
     // Work distribution, chosen per chunk size and per schedule (the analogue of choosing the

@@ -328,3 +328,20 @@ def test_staged_lowering_choice_and_limits():
 
 def P_bytes(st):
     return st["num_nodes"] * st["bytes_per_rank"]
+
+
+def test_hostile_sizes_and_enum_values_are_refused_not_trusted():
+    topo, ag = tp.ring(4), col.allgather(4, 1)
+    s = gen.greedy_bfs(topo, ag)
+    # element counts whose byte sizes do not fit 63 bits (chunk, rank buffer or the statistics' byte counts)
+    for epc in ((1 << 62) + 5, (1 << 63) - 1, 1 << 61):
+        assert plan_status(topo, ag, s, "f32", epc)[0] == "SCCL_ERR_INVALID_ARG"
+    assert plan_status(topo, ag, s, "f32", -1)[0] == "SCCL_ERR_INVALID_ARG"
+    name, st = plan_status(topo, ag, s, "f16", 1 << 40, options={"lowering": sccl.SCCL_LOWER_MEMORY})
+    assert name == "SCCL_OK" and st["bytes_per_rank"] == 4 * 2 * (1 << 40)      # large but representable
+    # an integer that is no sccl_dtype_t in the enum's place
+    sccl.DTYPE_CODES["not-a-dtype"] = 256
+    try:
+        assert plan_status(topo, ag, s, "not-a-dtype", 4)[0] == "SCCL_ERR_INVALID_ARG"
+    finally:
+        del sccl.DTYPE_CODES["not-a-dtype"]
