@@ -64,6 +64,43 @@ def test_random_case_validates_and_has_the_closed_form(seed):
                     assert (bufs[n].view(u)[c * epc:(c + 1) * epc] == pristine[owner].view(u)[c * epc:(c + 1) * epc]).all(), label
 
 
+@pytest.mark.parametrize("seed", SEEDS)
+def test_mutated_random_case_gets_the_oracles_verdict(seed):
+    """Break a valid random schedule in one place (a send's field, a dropped or repeated send, a step's rounds, a
+    bit of post): the library's host validation and the oracle's validator must name the same defect, or both accept."""
+    from helpers import VERDICT_TO_STATUS
+    from oracle.schedule import Schedule
+    from oracle.collective import Collective
+    label, topo, coll, sched, dtype, dist, epc = random_case(seed)
+    rng = np.random.default_rng(seed + 77)
+    P, G, S = coll.num_nodes, coll.num_chunks, sched.num_steps
+    for trial in range(12):
+        sends, rounds, post = sched.sends.copy(), list(sched.rounds), coll.post.copy()
+        kind = int(rng.integers(0, 6))
+        n = sends.shape[0]
+        if kind == 0 and n:
+            i, f = int(rng.integers(0, n)), int(rng.integers(0, 5))
+            hi = (G, P, P, S, 2)[f]
+            sends[i, f] = int(rng.integers(-1, hi + 1))
+        elif kind == 1 and n:
+            sends = np.delete(sends, int(rng.integers(0, n)), axis=0)
+        elif kind == 2 and n:
+            i = int(rng.integers(0, n))
+            sends = np.insert(sends, i, sends[i], axis=0)
+        elif kind == 3:
+            rounds[int(rng.integers(0, S))] = int(rng.integers(0, 3))
+        elif kind == 4:
+            post[int(rng.integers(0, G)), int(rng.integers(0, P))] ^= 1
+        elif kind == 5 and n > 1:
+            i, j = rng.integers(0, n, size=2)
+            sends[[i, j], 3] = sends[[j, i], 3]                 # two sends trade steps
+        m = Schedule(rounds, sends)
+        c = Collective(coll.name, P, G, coll.pre, post, coll.combining, coll.chunks_per_node)
+        want = VERDICT_TO_STATUS[validate(topo, c, m).verdict.value]
+        got, _ = plan_status(topo, c, m, dtype, 4)
+        assert got == want, (label, trial, kind)
+
+
 @pytest.mark.gpu
 @pytest.mark.parametrize("seed", SEEDS)
 @pytest.mark.parametrize("mode", ["sccl_execute", "sccl_execute_stepwise"])
