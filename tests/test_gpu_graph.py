@@ -54,3 +54,31 @@ def test_graph_replays_equal_the_oracle(lowering, epc):
             assert torch.equal(e.view(torch.int32), w.view(torch.int32))
     del graph
     sccl.sccl_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("lowering", [sccl.SCCL_LOWER_MEMORY, sccl.SCCL_LOWER_STAGED])
+def test_one_plan_on_two_streams_with_different_buffers(lowering):
+    """A plan holds no mutable state: two executes of it may run at the same time on two (default-priority) streams
+    as long as their rank buffers differ."""
+    import torch
+    topo = tp.hcm8()
+    ag = col.allgather(8, 2)
+    sched, coll = gen.compose_allreduce(gen.greedy_bfs(topo, ag), ag)
+    P, G, epc = 8, coll.num_chunks, 4 * 4099
+    plan = sccl.sccl_plan_create(*to_binding(topo, coll, sched, "f32", epc), options={"lowering": lowering})
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    sets, wants = [], []
+    for seed in (11, 12):
+        bufs = host_inputs("uniform", "f32", seed, P, G, epc)
+        want = [b.copy() for b in bufs]
+        ex.execute("f32", G, epc, sched, want)
+        wants.append(want)
+        sets.append([torch.from_numpy(b).cuda() for b in bufs])
+    torch.cuda.synchronize()
+    print(f"[case] two streams lowering={lowering}", flush=True)
+    for st, dev in zip(streams, sets):                      # back to back: the two kernels overlap on the device
+        sccl.sccl_execute(plan, dev, st)
+    torch.cuda.synchronize()
+    for dev, want in zip(sets, wants):
+        assert_same_bits(want, [d.cpu().numpy() for d in dev])
+    sccl.sccl_plan_destroy(plan)
