@@ -217,7 +217,9 @@ sccl_status_t sccl_plan_create_ex(const sccl_topology_t* topology, const sccl_co
  * The call enqueues one kernel and returns; it does not synchronise and does not allocate.  The
  * pointer array is read on the host during the call.  Nothing is launched
  * when the status is not SCCL_OK.  A plan is immutable: concurrent calls with
- * one plan are allowed as long as their buffers differ.
+ * one plan are allowed as long as their buffers differ.  Because the call does
+ * nothing but check its arguments on the host and enqueue one kernel, it may
+ * be made while `stream` is being captured into a HIP graph.
  */
 sccl_status_t sccl_execute(const sccl_plan_t* plan, void* const* rank_buffers, void* stream);
 
