@@ -289,7 +289,8 @@ def main():
         rows = []
         names = [("cfg1", workloads.WORKLOADS["cfg1"]), ("cfg2", workloads.WORKLOADS["cfg2"]),
                  ("cfg3", workloads.WORKLOADS["cfg3"]), ("cfg4", workloads.WORKLOADS["cfg4"]),
-                 ("cfg4b", workloads.WORKLOADS["cfg4b"]), ("alltoall", workloads.WORKLOADS["alltoall"])]
+                 ("cfg4b", workloads.WORKLOADS["cfg4b"])]
+        names += [(k, workloads.WORKLOADS[k]) for k in ("alltoall", "broadcast", "reduce", "gather", "scatter")]
         for coll in ("allgather", "allreduce"):
             for size in workloads.sweep_sizes():
                 names.append((f"cfg5 {coll} {size}", workloads.sweep_workload(coll, size)))

@@ -111,7 +111,18 @@ def extra_configurations():
     from . import synthesize as syn
     t = tp.dgx1()
     a2a = col.alltoall(8, 8)
-    return {"alltoall_dgx1": (t, a2a, syn.solve_instance(t, a2a, 3, 3))}
+    out = {"alltoall_dgx1": (t, a2a, syn.solve_instance(t, a2a, 3, 3))}
+    # the remaining collectives of Table 2, and Reduce by inversion (section 3.5), on the same graph: the
+    # latency-optimal rows the shortest-path generator reaches (Broadcast (2,2,2), Gather (1,2,2))
+    bc = col.broadcast(8, 2, 0)
+    s_bc = gen.greedy_route(t, bc)
+    out["broadcast_dgx1"] = (t, bc, s_bc)
+    out["reduce_dgx1"] = (t.reversed(), col.reduce(8, 2, 0), gen.invert(s_bc, bc))
+    ga = col.gather(8, 1, 0)
+    out["gather_dgx1"] = (t, ga, gen.greedy_route(t, ga))
+    sc = col.scatter(8, 8, 0)
+    out["scatter_dgx1"] = (t, sc, gen.greedy_route(t, sc))
+    return out
 
 
 def main():

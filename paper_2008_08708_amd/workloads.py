@@ -38,6 +38,11 @@ WORKLOADS: Dict[str, Workload] = {
     # beyond the five configurations: Alltoall, the paper's row (8,3,3) on its DGX-1 graph; 8 ranks, 8 MiB chunks
     # (a 64 MiB send buffer per rank) in a compact layout of 20 chunk positions per rank
     "alltoall": Workload("alltoall", "alltoall_dgx1", "f32", "uniform", 6, 20 * 8 * MiB, True),
+    # and the other collectives of the paper's Table 2 on the same graph, 64 MiB rank buffers
+    "broadcast": Workload("broadcast", "broadcast_dgx1", "f32", "uniform", 7, 64 * MiB, True),
+    "reduce": Workload("reduce", "reduce_dgx1", "f32", "uniform", 8, 64 * MiB, False),
+    "gather": Workload("gather", "gather_dgx1", "f32", "uniform", 9, 64 * MiB, True),
+    "scatter": Workload("scatter", "scatter_dgx1", "f32", "uniform", 10, 64 * MiB, True),
 }
 
 

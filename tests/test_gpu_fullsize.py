@@ -4,8 +4,9 @@ The oracle cannot run 4-16 GiB cases in seconds, so it runs on SAMPLED element w
 independent, so executing the schedule on the windows alone (same bits in, read back from the device
 inputs before the run) must give the bits the GPU left in those windows.  Windows sit at the start of
 a chunk, across a tile boundary in the middle, and at the ragged end.  On top of that, properties that
-hold at any size are checked on the whole buffers: Allgather's closed form out[n][c] = in[c mod P][c],
-Alltoall's out[(c div P) mod P][c] = in[c mod P][c], and all ranks bitwise equal after Allreduce.  Tolerance: 0 ulp (see test_gpu_parity.py).
+hold at any size are checked on the whole buffers: the closed form of every non-combining collective (wherever
+post wants chunk c it equals the chunk of its holder in pre: Allgather out[n][c] = in[c mod P][c], Alltoall
+out[(c div P) mod P][c] = in[c mod P][c], Broadcast, Gather, Scatter alike), and all ranks bitwise equal after Allreduce.  Tolerance: 0 ulp (see test_gpu_parity.py).
 """
 import numpy as np
 import pytest
@@ -19,7 +20,9 @@ pytestmark = pytest.mark.gpu
 
 CASES = [("cfg2", workloads.WORKLOADS["cfg2"]), ("cfg3", workloads.WORKLOADS["cfg3"]),
          ("cfg4", workloads.WORKLOADS["cfg4"]), ("cfg4b", workloads.WORKLOADS["cfg4b"]),
-         ("alltoall", workloads.WORKLOADS["alltoall"])]
+         ("alltoall", workloads.WORKLOADS["alltoall"]), ("broadcast", workloads.WORKLOADS["broadcast"]),
+         ("reduce", workloads.WORKLOADS["reduce"]), ("gather", workloads.WORKLOADS["gather"]),
+         ("scatter", workloads.WORKLOADS["scatter"])]
 for coll in ("allgather", "allreduce"):
     for size in (1 << 10, 1 << 16, 1 << 22, 1 << 28, 1 << 30):
         CASES.append((f"cfg5-{coll}-{size}", workloads.sweep_workload(coll, size)))
@@ -61,8 +64,9 @@ def test_full_size_sampled_windows_and_global_properties(label, wl):
 
     host = gather(work)                                   # the oracle's inputs: the same bits the GPU starts from
     owners = None
-    if sf.collective in ("allgather", "alltoall"):         # both start Scattered: chunk c at rank c mod P
-        owners = [work[c % P].view(K, epc)[position(c, c % P)].clone() for c in range(G)]
+    if not sf.combining:                                   # the chunk as its holder in pre has it before the run
+        holder = [int(np.nonzero(sf.pre[c])[0][0]) for c in range(G)]
+        owners = [work[holder[c]].view(K, epc)[position(c, holder[c])].clone() for c in range(G)]
     sccl.sccl_execute(plan, work)
     torch.cuda.synchronize()
     ex.execute(wl.dtype, G, wtot, Schedule(sf.rounds, sf.sends), host, threads=8,
@@ -72,18 +76,19 @@ def test_full_size_sampled_windows_and_global_properties(label, wl):
     for n in range(P):
         bad = np.nonzero(got[n].view(u) != host[n].view(u))[0]
         assert bad.size == 0, f"rank {n}: {bad.size} sampled elements differ, first at {bad[0]}"
-    if sf.collective == "allgather":
-        for n in range(P):
-            v = work[n].view(G, epc)
-            for c in range(G):
-                assert torch.equal(v[c], owners[c]), f"rank {n} chunk {c} is not the owner's chunk"
-    elif sf.collective == "alltoall":                      # Transpose: chunk c ends at rank (c div P) mod P
-        for c in range(G):
-            n = (c // P) % P
-            assert torch.equal(work[n].view(K, epc)[position(c, n)], owners[c]), f"chunk {c} did not arrive at rank {n}"
-    else:
+    if not sf.combining:                                   # closed form of every non-combining collective (Table 2):
+        for c in range(G):                                 # wherever post wants chunk c, it is its pre-holder's chunk
+            for n in range(P):
+                if sf.post[c, n]:
+                    assert torch.equal(work[n].view(K, epc)[position(c, n)], owners[c]), f"chunk {c} at rank {n}"
+    elif sf.collective == "allreduce":
         ref = work[0].view(torch.int32 if wl.elem_bytes == 4 else torch.int16)
         for n in range(1, P):
             assert torch.equal(work[n].view(ref.dtype), ref), f"rank {n} differs from rank 0"
         assert not torch.isnan(work[0]).any()
+    else:                                                  # Reduce: the sum sits where post says; no NaN there
+        for c in range(G):
+            for n in range(P):
+                if sf.post[c, n]:
+                    assert not torch.isnan(work[n].view(K, epc)[position(c, n)]).any()
     sccl.sccl_plan_destroy(plan)
