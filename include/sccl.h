@@ -137,8 +137,10 @@ typedef struct {
  *                      3.6) and not the bytes.  Needs room for one slice of every cell of a chunk and fewer
  *                      than 256 dependency levels per chunk: SCCL_ERR_INVALID_ARG if asked for explicitly
  *                      and that does not hold.
- *   SCCL_LOWER_AUTO    staged when possible and the P rank buffers together are at most 16 MiB (the measured
- *                      crossover: below it the time is launch plus latency and no bandwidth claim applies),
+ *   SCCL_LOWER_AUTO    from measured crossovers: staged when possible and either the P rank buffers together
+ *                      are at most 512 KiB (launch overhead dominates; staged never loses), or the schedule
+ *                      has long chains that levels shorten (some chunk has at least 8 groups and at least
+ *                      twice as many groups as levels) and the staged kernel has at most 4096 work items;
  *                      through memory otherwise. */
 #define SCCL_LOWER_AUTO   0
 #define SCCL_LOWER_MEMORY 1
@@ -184,6 +186,7 @@ typedef struct {
     int32_t num_cells_stored;      /* of those, written by some send */
     int32_t num_levels;            /* length of the longest chain of dependent groups (of any one chunk) */
     int32_t max_level_tasks;       /* most cell writes any one level of any one chunk performs */
+    int32_t max_chunk_groups;      /* most groups any one chunk has (its chain in the through-memory kernel) */
     int32_t slice_vectors, staged_threads;
     int32_t staged_lds_bytes;      /* local data share one workgroup uses */
     int64_t num_slices;            /* staged work items: G * ceil(vectors per chunk / slice_vectors) */

@@ -137,6 +137,7 @@ bool build_staged_tables(const sccl_plan& plan, sccl_staged* out) {
         sg.n_cells += n_cells; sg.n_in += n_in; sg.n_out += n_out; sg.n_tasks += n_tasks;
         sg.n_levels = std::max(sg.n_levels, n_levels);
         sg.max_level_tasks = std::max(sg.max_level_tasks, widest);
+        sg.max_chunk_groups = std::max(sg.max_chunk_groups, (int32_t)n_groups);
         sg.max_chunk_cells = std::max(sg.max_chunk_cells, n_cells);
         sg.max_chunk_in = std::max(sg.max_chunk_in, n_in);
         sg.max_chunk_out = std::max(sg.max_chunk_out, n_out);
@@ -509,13 +510,20 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
         }
     }
     if (want_lowering == SCCL_LOWER_STAGED && !sg.available) return SCCL_ERR_INVALID_ARG;
-    const bool small = (int64_t)P * st.bytes_per_rank <= STAGED_AUTO_TOTAL_BYTES;
-    plan->lowering = (want_lowering == SCCL_LOWER_STAGED || (want_lowering == SCCL_LOWER_AUTO && sg.available && small))
+    // SCCL_LOWER_AUTO, from the measured crossovers: the staged kernel never loses while launch overhead dominates
+    // (tiny totals); beyond that it wins where a chunk's chain of groups is long AND shortens when groups of one
+    // level run together (at least 8 groups and twice as many groups as levels: tree-shaped schedules on multi-hop
+    // topologies, not rings and not two-step schedules), and only while its single-wavefront work items stay few.
+    const bool tiny = (int64_t)P * st.bytes_per_rank <= STAGED_AUTO_TINY_BYTES;
+    const bool long_chains = sg.max_chunk_groups >= 8 && sg.max_chunk_groups >= 2 * sg.n_levels;
+    const bool few_items = sg.num_slices <= STAGED_AUTO_MAX_ITEMS;
+    const bool automatic = sg.available && (tiny || (long_chains && few_items));
+    plan->lowering = (want_lowering == SCCL_LOWER_STAGED || (want_lowering == SCCL_LOWER_AUTO && automatic))
                          ? SCCL_LOWER_STAGED : SCCL_LOWER_MEMORY;
     st.lowering = plan->lowering;
     st.staged_available = sg.available ? 1 : 0;
     st.num_cells = sg.n_cells; st.num_cells_loaded = sg.n_in; st.num_cells_stored = sg.n_out;
-    st.num_levels = sg.n_levels; st.max_level_tasks = sg.max_level_tasks;
+    st.num_levels = sg.n_levels; st.max_level_tasks = sg.max_level_tasks; st.max_chunk_groups = sg.max_chunk_groups;
     st.slice_vectors = sg.available ? (1 << sg.log_slice_vectors) : 0;
     st.staged_threads = sg.threads;
     st.staged_lds_bytes = sg.lds_bytes;

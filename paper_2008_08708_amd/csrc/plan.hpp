@@ -42,12 +42,14 @@ constexpr int32_t STAGED_HEADER_WORDS = 8;
 constexpr int32_t STAGED_TASK_WORDS = 8;
 constexpr int32_t STAGED_MAX_LEVELS = 256;                // a wavefront keeps the level table in four registers per lane
 constexpr int64_t STAGED_LDS_LIMIT = 160 * 1024;          // local data share of one gfx950 compute unit
-constexpr int64_t STAGED_AUTO_TOTAL_BYTES = 16ll << 20;   // measured crossover with the through-memory kernel
+constexpr int64_t STAGED_AUTO_TINY_BYTES = 512ll << 10;   // all rank buffers together: launch overhead dominates
+constexpr int64_t STAGED_AUTO_MAX_ITEMS = 4096;           // work items (16 per compute unit) up to which long chains pay
 
 struct sccl_staged {
     bool available = false;
     // totals over the chunks (statistics) and maxima over the chunks (sizes a workgroup needs)
     int32_t n_cells = 0, n_in = 0, n_out = 0, n_levels = 0, n_tasks = 0, max_level_tasks = 0;
+    int32_t max_chunk_groups = 0;
     int32_t max_chunk_cells = 0, max_chunk_in = 0, max_chunk_out = 0, max_block_words = 0, cell_words_room = 0;
     std::vector<int32_t> table;
     // launch shape

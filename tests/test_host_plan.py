@@ -310,6 +310,15 @@ def test_staged_lowering_choice_and_limits():
     for epc, want in ((1 << 12, sccl.SCCL_LOWER_STAGED), (1 << 13, sccl.SCCL_LOWER_MEMORY)):
         _, st = plan_status(topo, arc, ar, "f32", epc)
         assert P_bytes(st) == 16 * 64 * epc * 4 and st["lowering"] == want
+    # rings and two-step schedules have no chain that levels shorten: staged only while tiny (512 KiB over all ranks)
+    ring, rag = tp.ring(8), col.allgather(8, 4)
+    rar, rarc = gen.compose_allreduce(gen.ring_allgather(8, 4), rag)
+    for epc, want in ((512, sccl.SCCL_LOWER_STAGED), (1024, sccl.SCCL_LOWER_MEMORY)):      # 32 chunks x 8 ranks x epc x 4 B
+        _, st = plan_status(ring, rarc, rar, "f32", epc)
+        assert st["lowering"] == want and st["max_chunk_groups"] == st["num_levels"] == 14
+    k8, kag = tp.complete(8), col.allgather(8, 1)
+    kar, karc = gen.compose_allreduce(gen.greedy_bfs(k8, kag), kag)
+    assert plan_status(k8, karc, kar, "f32", 1 << 16)[1]["lowering"] == sccl.SCCL_LOWER_MEMORY       # 2 groups per chunk
     # explicit choices
     st = plan_status(topo, arc, ar, "f32", 1 << 14, options={"lowering": sccl.SCCL_LOWER_STAGED})[1]
     assert st["lowering"] == sccl.SCCL_LOWER_STAGED and st["slice_vectors"] == 16 and st["staged_threads"] == 64
