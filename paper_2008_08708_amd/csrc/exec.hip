@@ -664,13 +664,24 @@ sccl_status_t sccl_plan_create_ex(const sccl_topology_t* topology, const sccl_co
         if (!good) { sccl_plan_destroy(plan); return SCCL_ERR_DEVICE; }
         sccl_staged& sg = plan->staged;
         if (sg.available) {
-            const size_t tb = sg.table.size() * sizeof(int32_t);
             staged_fn sfn = pick_staged_kernel(plan->dtype, plan->vector_bytes);
-            // more than 64 KiB of dynamic local data share has to be asked for, per kernel
-            const bool staged_ok =
-                hipFuncSetAttribute((const void*)sfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)STAGED_LDS_LIMIT) == hipSuccess &&
-                hipMalloc((void**)&plan->d_staged, tb) == hipSuccess &&
-                hipMemcpy(plan->d_staged, sg.table.data(), tb, hipMemcpyHostToDevice) == hipSuccess;
+            // More than 64 KiB of dynamic local data share has to be asked for, per kernel.  If the runtime
+            // refuses, plans that need more cannot be staged: they fall back to the through-memory kernel
+            // unless the caller demanded the staged one.
+            if (sg.lds_bytes > 64 * 1024 &&
+                hipFuncSetAttribute((const void*)sfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)STAGED_LDS_LIMIT) != hipSuccess) {
+                (void)hipGetLastError();
+                if (plan->opts.lowering == SCCL_LOWER_STAGED) { sccl_plan_destroy(plan); return SCCL_ERR_DEVICE; }
+                sg.available = false;
+                plan->lowering = SCCL_LOWER_MEMORY;
+                plan->stats.lowering = SCCL_LOWER_MEMORY;
+                plan->stats.staged_available = 0;
+            }
+        }
+        if (sg.available) {
+            const size_t tb = sg.table.size() * sizeof(int32_t);
+            const bool staged_ok = hipMalloc((void**)&plan->d_staged, tb) == hipSuccess &&
+                                   hipMemcpy(plan->d_staged, sg.table.data(), tb, hipMemcpyHostToDevice) == hipSuccess;
             if (!staged_ok) { sccl_plan_destroy(plan); return SCCL_ERR_DEVICE; }
             // Latency bound: one workgroup per work item while the hardware can queue them (32 per CU), the
             // grid-stride loop only beyond that
