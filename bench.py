@@ -378,6 +378,15 @@ def main():
                 f.write(f"\n{coll}: fitted alpha = {alpha * 1e6:.3f} us per step, beta = {beta * 1e12:.4f} ps per byte "
                         f"(1 / beta = {1e-9 / beta if beta > 0 else float('inf'):.0f} GB/s per link-equivalent)\n")
                 print(f"[report] {coll}: alpha {alpha * 1e6:.3f} us, beta {beta * 1e12:.4f} ps/B", file=sys.stderr, flush=True)
+        with open(args.report, "a") as f:
+            f.write("\nContext, not a target: the paper gives no absolute time or bandwidth for executing a schedule in its "
+                    "text, only speedups measured across eight GPUs over their links (section 5.5): Allgather up to 2.2x "
+                    "(small) and 1.14x (large) over NCCL 2.7.8, Allreduce up to 1.8x (small, the 8-chunk algorithm) and 1.06x "
+                    "(large, the 48-chunk algorithm), Alltoall more than 6.8x (large) over point-to-point copies, on a DGX-1 "
+                    "(8 x V100, six 25 GB/s NVLink ports per GPU); Allgather faster than RCCL only at large sizes on a Gigabyte "
+                    "Z52 (8 x MI50, xGMI about 33 GB/s, PCIe 4 about 27 GB/s).  Nothing here reproduces an inter-GPU link: the "
+                    "figures above are one MI355X moving P virtual ranks' buffers inside its own HBM "
+                    f"(peak {HBM_PEAK_GBS / 1000:.0f} TB/s).\n")
     print(json.dumps(line), flush=True)
 
 
