@@ -48,8 +48,10 @@ typedef enum {
     SCCL_ERR_ALIGNMENT = 8,        /* a rank buffer is not 16-byte aligned */
     SCCL_ERR_OVERLAP = 9,          /* two rank buffers overlap */
     SCCL_ERR_NOMEM = 10,
-    SCCL_ERR_DEVICE = 11           /* a HIP call failed, execute on a host-only plan, or execute while another
+    SCCL_ERR_DEVICE = 11,          /* a HIP call failed, execute on a host-only plan, or execute while another
                                       device than the plan's is current */
+    SCCL_ERR_SCRATCH = 12          /* sccl_execute_static only: the plan's step table does not fit the library's
+                                      static device array of SCCL_STATIC_SCRATCH_BYTES */
 } sccl_status_t;
 
 typedef enum {
@@ -190,6 +192,7 @@ typedef struct {
     int32_t slice_vectors, staged_threads;
     int32_t staged_lds_bytes;      /* local data share one workgroup uses */
     int64_t num_slices;            /* staged work items: G * ceil(vectors per chunk / slice_vectors) */
+    int64_t static_table_bytes;    /* bytes of the step table sccl_execute_static would place in its static array */
 } sccl_stats_t;
 
 typedef struct sccl_plan sccl_plan_t;
@@ -238,6 +241,29 @@ sccl_status_t sccl_execute(const sccl_plan_t* plan, void* const* rank_buffers, v
  */
 sccl_status_t sccl_execute_stepwise(const sccl_plan_t* plan, void* const* rank_buffers, void* stream);
 sccl_status_t sccl_execute_memcpy(const sccl_plan_t* plan, void* const* rank_buffers, void* stream);
+
+/*
+ * sccl_execute for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same checks, same kernels and same results as
+ * sccl_execute, but the step table the kernel walks is not the copy sccl_plan_create uploaded: it lives in a
+ * static device array of SCCL_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU the
+ * library runs on holds its own copy until the process ends).  So the plan may be a SCCL_PLAN_HOST_ONLY plan,
+ * whose creation touched no device; with such a plan no call of this library ever allocates device memory.
+ *
+ * The call (1) returns SCCL_ERR_SCRATCH, before anything else is looked at and with nothing enqueued, when the
+ * table of the plan's lowering is larger than the array (sccl_stats_t.static_table_bytes says how large it is);
+ * (2) checks the buffers like sccl_execute; (3) writes the table into the array with small kernels enqueued on
+ * `stream`, one per 3.5 KiB of table (the words travel as kernel arguments: no copy from host memory and no
+ * staging buffer is involved), on every call, because the array keeps whatever the last call left there;
+ * (4) enqueues the plan's kernel on `stream`.  It calls no hipMalloc, no hipFree, no memset and no routine that
+ * allocates, and does not synchronise.  The launch shape is sized for the current device.
+ *
+ * All calls on one GPU share the one array: calls on different streams, or from different threads, whose
+ * work may overlap on the GPU race for it.  Serialise them on one stream (or with events).  Under graph
+ * capture the table writes are captured too, by value, so a replay is correct whatever ran in between.
+ */
+#define SCCL_STATIC_SCRATCH_BYTES (256 * 1024)
+sccl_status_t sccl_execute_static(const sccl_plan_t* plan, void* const* rank_buffers, void* stream);
 
 /* S, R, k, group counts, algorithmic byte counts and the launch shape. */
 sccl_status_t sccl_plan_stats(const sccl_plan_t* plan, sccl_stats_t* out_stats);

@@ -29,6 +29,7 @@
 #include <algorithm>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "plan.hpp"
@@ -706,11 +707,8 @@ sccl_status_t sccl_plan_create(const sccl_topology_t* topology, const sccl_colle
     return sccl_plan_create_ex(topology, collective, schedule, nullptr, out_plan);
 }
 
-static sccl_status_t check_buffers(const sccl_plan_t* plan, void* const* rank_buffers) {
-    if (!plan || !rank_buffers) return SCCL_ERR_INVALID_ARG;
-    if (plan->device < 0) return SCCL_ERR_DEVICE;
-    int current = -1;                                    // the step tables live on the device the plan was made on
-    if (hipGetDevice(&current) != hipSuccess || current != plan->device) return SCCL_ERR_DEVICE;
+// Alignment and pairwise disjointness of the P rank buffers (host arithmetic on the pointer values only).
+static sccl_status_t check_pointers(const sccl_plan_t* plan, void* const* rank_buffers) {
     const int32_t P = plan->P;
     const uint64_t bytes = (uint64_t)plan->stats.bytes_per_rank;
     for (int32_t n = 0; n < P; n++) {
@@ -723,6 +721,14 @@ static sccl_status_t check_buffers(const sccl_plan_t* plan, void* const* rank_bu
             if (a == b || (a < b ? a + bytes > b : b + bytes > a)) return SCCL_ERR_OVERLAP;
         }
     return SCCL_OK;
+}
+
+static sccl_status_t check_buffers(const sccl_plan_t* plan, void* const* rank_buffers) {
+    if (!plan || !rank_buffers) return SCCL_ERR_INVALID_ARG;
+    if (plan->device < 0) return SCCL_ERR_DEVICE;
+    int current = -1;                                    // the step tables live on the device the plan was made on
+    if (hipGetDevice(&current) != hipSuccess || current != plan->device) return SCCL_ERR_DEVICE;
+    return check_pointers(plan, rank_buffers);
 }
 
 sccl_status_t sccl_execute_stepwise(const sccl_plan_t* plan, void* const* rank_buffers, void* stream) {
@@ -764,11 +770,14 @@ sccl_status_t sccl_execute_memcpy(const sccl_plan_t* plan, void* const* rank_buf
     return SCCL_OK;
 }
 
-static sccl_status_t launch_staged(const sccl_plan_t* plan, void* const* rank_buffers, void* stream) {
+// The two launches of sccl_execute, with the table and the grid passed in: sccl_execute passes the plan's own
+// device copy, sccl_execute_static the library's static array.
+static sccl_status_t launch_staged(const sccl_plan_t* plan, const int32_t* table, int32_t grid,
+                                   void* const* rank_buffers, void* stream) {
     const sccl_staged& sg = plan->staged;
     StagedArgs args;
     std::memset(&args, 0, sizeof(args));
-    args.table = plan->d_staged;
+    args.table = table;
     args.chunk_bytes = plan->stats.chunk_bytes;
     args.num_items = sg.num_slices;
     args.vecs_per_chunk = plan->vecs_per_chunk;
@@ -778,27 +787,118 @@ static sccl_status_t launch_staged(const sccl_plan_t* plan, void* const* rank_bu
     args.cell_words_room = sg.cell_words_room;
     for (int32_t n = 0; n < plan->P; n++) args.bufs[n] = (char*)rank_buffers[n];
     staged_fn fn = pick_staged_kernel(plan->dtype, plan->vector_bytes);
-    hipLaunchKernelGGL(fn, dim3((unsigned)sg.grid), dim3((unsigned)sg.threads), (size_t)sg.lds_bytes, (hipStream_t)stream, args);
+    hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3((unsigned)sg.threads), (size_t)sg.lds_bytes, (hipStream_t)stream, args);
+    return hipGetLastError() == hipSuccess ? SCCL_OK : SCCL_ERR_DEVICE;
+}
+
+static sccl_status_t launch_memory(const sccl_plan_t* plan, const int32_t* prog, const int32_t* chunk_off, int32_t grid,
+                                   void* const* rank_buffers, void* stream) {
+    ExecArgs args;
+    std::memset(&args, 0, sizeof(args));
+    args.prog = prog;
+    args.chunk_off = chunk_off;
+    args.chunk_bytes = plan->stats.chunk_bytes;
+    args.num_items = plan->num_items;
+    args.tiles_per_chunk = plan->tiles_per_chunk;
+    for (int32_t n = 0; n < plan->P; n++) args.bufs[n] = (char*)rank_buffers[n];
+    kernel_fn fn = pick_kernel(plan->dtype, plan->vector_bytes, plan->vectors_per_thread);
+    hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3((unsigned)plan->block_threads), 0, (hipStream_t)stream, args);
     return hipGetLastError() == hipSuccess ? SCCL_OK : SCCL_ERR_DEVICE;
 }
 
 sccl_status_t sccl_execute(const sccl_plan_t* plan, void* const* rank_buffers, void* stream) {
     const sccl_status_t chk = check_buffers(plan, rank_buffers);
     if (chk != SCCL_OK) return chk;
-    const int32_t P = plan->P;
     if (plan->num_items == 0 || plan->prog.empty()) return SCCL_OK;     // nothing to move
-    if (plan->lowering == SCCL_LOWER_STAGED) return launch_staged(plan, rank_buffers, stream);
-    ExecArgs args;
-    std::memset(&args, 0, sizeof(args));
-    args.prog = plan->d_prog;
-    args.chunk_off = plan->d_chunk_off;
-    args.chunk_bytes = plan->stats.chunk_bytes;
-    args.num_items = plan->num_items;
-    args.tiles_per_chunk = plan->tiles_per_chunk;
-    for (int32_t n = 0; n < P; n++) args.bufs[n] = (char*)rank_buffers[n];
-    kernel_fn fn = pick_kernel(plan->dtype, plan->vector_bytes, plan->vectors_per_thread);
-    hipLaunchKernelGGL(fn, dim3((unsigned)plan->grid), dim3((unsigned)plan->block_threads), 0, (hipStream_t)stream, args);
-    return hipGetLastError() == hipSuccess ? SCCL_OK : SCCL_ERR_DEVICE;
+    if (plan->lowering == SCCL_LOWER_STAGED) return launch_staged(plan, plan->d_staged, plan->staged.grid, rank_buffers, stream);
+    return launch_memory(plan, plan->d_prog, plan->d_chunk_off, plan->grid, rank_buffers, stream);
+}
+
+// ---- sccl_execute_static: the step table in a static device array instead of memory the plan allocated.
+//
+// `scratch` below is part of the code object, so every GPU that loads the library has its own copy at its own
+// address, from load time to the end of the process.  In host code the NAME is only a handle for
+// hipGetSymbolAddress: the address kernels are given is the one that call returns, looked up once per device
+// with that device current, and kept in static_devices[].
+constexpr int32_t STATIC_SCRATCH_WORDS = SCCL_STATIC_SCRATCH_BYTES / 4;
+static __device__ __align__(256) int32_t scratch[STATIC_SCRATCH_WORDS];
+
+// Table words travel as kernel arguments (by value, read by the kernel from its argument block), so writing
+// the table needs no host-to-device copy and is captured by value when the stream is being captured.
+constexpr int32_t SCRATCH_WRITE_WORDS = 896;              // 3.5 KiB of a 4 KiB argument block
+struct ScratchWriteArgs {
+    int32_t* dst;                                         // where in the static array
+    int32_t count, pad;
+    int32_t words[SCRATCH_WRITE_WORDS];
+};
+
+__global__ void __launch_bounds__(256) sccl_scratch_write_kernel(const ScratchWriteArgs a) {
+    for (int32_t i = (int32_t)threadIdx.x; i < a.count; i += 256) a.dst[i] = a.words[i];
+}
+
+constexpr int MAX_STATIC_DEVICES = 64;
+struct StaticDevice {
+    int32_t* ptr = nullptr;                               // device address of `scratch` on this GPU
+    int num_cus = 0;
+};
+static StaticDevice static_devices[MAX_STATIC_DEVICES];
+static std::mutex static_mutex;
+
+sccl_status_t sccl_execute_static(const sccl_plan_t* plan, void* const* rank_buffers, void* stream) {
+    if (!plan || !rank_buffers) return SCCL_ERR_INVALID_ARG;
+    const bool staged = plan->lowering == SCCL_LOWER_STAGED;
+    const std::vector<int32_t>& image = staged ? plan->staged.table : plan->static_image;
+    if (image.size() > (size_t)STATIC_SCRATCH_WORDS) return SCCL_ERR_SCRATCH;
+    const sccl_status_t chk = check_pointers(plan, rank_buffers);
+    if (chk != SCCL_OK) return chk;
+    if (plan->num_items == 0 || plan->prog.empty()) return SCCL_OK;     // nothing to move
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_STATIC_DEVICES) return SCCL_ERR_DEVICE;
+
+    std::lock_guard<std::mutex> lock(static_mutex);
+    StaticDevice& sd = static_devices[dev];
+    if (!sd.ptr) {                                        // first call on this GPU
+        int32_t* p = nullptr;
+        int cus = 0;
+        if (hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)) != hipSuccess || !p ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+            (void)hipGetLastError();
+            return SCCL_ERR_DEVICE;
+        }
+        sd.num_cus = cus;
+        sd.ptr = p;
+    }
+    if (staged && plan->staged.lds_bytes > 64 * 1024 &&
+        hipFuncSetAttribute((const void*)pick_staged_kernel(plan->dtype, plan->vector_bytes),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)STAGED_LDS_LIMIT) != hipSuccess) {
+        (void)hipGetLastError();
+        return SCCL_ERR_DEVICE;
+    }
+
+    // The table first, on the same stream, every time: the array is shared by every call on this GPU (and by
+    // replays of graphs that captured one), so nothing can be assumed about what it holds.
+    {
+        ScratchWriteArgs w;
+        for (size_t at = 0; at < image.size(); at += SCRATCH_WRITE_WORDS) {
+            const size_t n = std::min(image.size() - at, (size_t)SCRATCH_WRITE_WORDS);
+            w.dst = sd.ptr + at;
+            w.count = (int32_t)n; w.pad = 0;
+            std::memcpy(w.words, image.data() + at, n * sizeof(int32_t));
+            hipLaunchKernelGGL(sccl_scratch_write_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, w);
+            if (hipGetLastError() != hipSuccess) return SCCL_ERR_DEVICE;
+        }
+    }
+    sccl_status_t st;
+    if (staged) {
+        int64_t grid = plan->opts.max_workgroups > 0 ? plan->opts.max_workgroups : (int64_t)sd.num_cus * 32;
+        grid = std::min(grid, plan->staged.num_slices);
+        st = launch_staged(plan, sd.ptr, (int32_t)grid, rank_buffers, stream);
+    } else {
+        int64_t grid = plan->opts.max_workgroups > 0 ? plan->opts.max_workgroups : (int64_t)sd.num_cus;
+        grid = std::min(grid, plan->num_items);
+        st = launch_memory(plan, sd.ptr + plan->static_prog_off, sd.ptr, (int32_t)grid, rank_buffers, stream);
+    }
+    return st;
 }
 
 sccl_status_t sccl_plan_stats(const sccl_plan_t* plan, sccl_stats_t* out_stats) {
@@ -831,6 +931,7 @@ const char* sccl_status_string(sccl_status_t status) {
         case SCCL_ERR_OVERLAP: return "SCCL_ERR_OVERLAP";
         case SCCL_ERR_NOMEM: return "SCCL_ERR_NOMEM";
         case SCCL_ERR_DEVICE: return "SCCL_ERR_DEVICE";
+        case SCCL_ERR_SCRATCH: return "SCCL_ERR_SCRATCH";
     }
     return "SCCL_ERR_UNKNOWN";
 }

@@ -528,5 +528,12 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
     st.staged_threads = sg.threads;
     st.staged_lds_bytes = sg.lds_bytes;
     st.num_slices = sg.num_slices;
+
+    // ---- the table as sccl_execute_static places it in the static device array
+    plan->static_image.assign(plan->chunk_off.begin(), plan->chunk_off.end());
+    while (plan->static_image.size() % 4) plan->static_image.push_back(0);
+    plan->static_prog_off = (int32_t)plan->static_image.size();
+    plan->static_image.insert(plan->static_image.end(), plan->prog.begin(), plan->prog.end());
+    st.static_table_bytes = 4 * (int64_t)(plan->lowering == SCCL_LOWER_STAGED ? sg.table.size() : plan->static_image.size());
     return SCCL_OK;
 }

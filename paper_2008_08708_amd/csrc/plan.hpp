@@ -99,6 +99,11 @@ struct sccl_plan {
     sccl_staged staged;
     int32_t lowering = SCCL_LOWER_MEMORY;
     int32_t* d_staged = nullptr;
+    // what sccl_execute_static writes into the library's static device array when the plan is lowered through
+    // memory: chunk_off (padded to a multiple of four words), then prog at word static_prog_off.  (A staged plan
+    // places staged.table there.)
+    std::vector<int32_t> static_image;
+    int32_t static_prog_off = 0;
 };
 
 // Validates the schedule and fills everything except the device fields and `grid`.

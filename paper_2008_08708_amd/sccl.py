@@ -19,7 +19,8 @@ SCCL_MAX_RANKS = 64
 SCCL_OK = 0
 STATUS_NAMES = ["SCCL_OK", "SCCL_ERR_INVALID_ARG", "SCCL_ERR_TOPOLOGY", "SCCL_ERR_SEND_NO_SOURCE",
                 "SCCL_ERR_SEND_NO_LINK", "SCCL_ERR_BANDWIDTH", "SCCL_ERR_POSTCONDITION", "SCCL_ERR_HAZARD",
-                "SCCL_ERR_ALIGNMENT", "SCCL_ERR_OVERLAP", "SCCL_ERR_NOMEM", "SCCL_ERR_DEVICE"]
+                "SCCL_ERR_ALIGNMENT", "SCCL_ERR_OVERLAP", "SCCL_ERR_NOMEM", "SCCL_ERR_DEVICE", "SCCL_ERR_SCRATCH"]
+SCCL_STATIC_SCRATCH_BYTES = 256 * 1024
 SCCL_I32, SCCL_F32, SCCL_F16 = 0, 1, 2
 DTYPE_CODES = {"i32": SCCL_I32, "f32": SCCL_F32, "f16": SCCL_F16}
 SCCL_COPY, SCCL_REDUCE_SUM = 0, 1
@@ -77,14 +78,15 @@ class sccl_stats_t(ctypes.Structure):
                 ("num_cells_loaded", ctypes.c_int32), ("num_cells_stored", ctypes.c_int32),
                 ("num_levels", ctypes.c_int32), ("max_level_tasks", ctypes.c_int32), ("max_chunk_groups", ctypes.c_int32),
                 ("slice_vectors", ctypes.c_int32), ("staged_threads", ctypes.c_int32),
-                ("staged_lds_bytes", ctypes.c_int32), ("num_slices", ctypes.c_int64)]
+                ("staged_lds_bytes", ctypes.c_int32), ("num_slices", ctypes.c_int64),
+                ("static_table_bytes", ctypes.c_int64)]
 
     def as_dict(self):
         return {name: getattr(self, name) for name, _ in self._fields_}
 
 
 EXPORTS = ["sccl_plan_create", "sccl_plan_create_ex", "sccl_execute", "sccl_execute_stepwise", "sccl_execute_memcpy",
-           "sccl_plan_stats", "sccl_plan_destroy",
+           "sccl_execute_static", "sccl_plan_stats", "sccl_plan_destroy",
            "sccl_status_string", "sccl_copy_kernel", "sccl_plan_cost", "sccl_select_plan", "sccl_cost_fit"]
 
 _lib = None
@@ -111,7 +113,7 @@ def lib() -> ctypes.CDLL:
                                           ctypes.POINTER(ctypes.c_void_p)]
         L.sccl_execute.restype = ctypes.c_int
         L.sccl_execute.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p]
-        for fn in (L.sccl_execute_stepwise, L.sccl_execute_memcpy):
+        for fn in (L.sccl_execute_stepwise, L.sccl_execute_memcpy, L.sccl_execute_static):
             fn.restype = ctypes.c_int
             fn.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p]
         L.sccl_plan_stats.restype = ctypes.c_int
@@ -172,6 +174,7 @@ class Plan:
 
     def __init__(self, handle: int):
         self.handle = ctypes.c_void_p(handle)
+        self.num_nodes = 0                                 # P: how many rank buffers an execute call must be given
 
     def __del__(self):
         try:
@@ -223,7 +226,9 @@ def sccl_plan_create(topology: Topology, collective: Collective, schedule: Sched
         st = L.sccl_plan_create(ctypes.byref(topo), ctypes.byref(coll), ctypes.byref(sched), ctypes.byref(out))
     if st != SCCL_OK:
         raise ScclError(st, "sccl_plan_create")
-    return Plan(out.value)
+    plan = Plan(out.value)
+    plan.num_nodes = sccl_plan_stats(plan)["num_nodes"]
+    return plan
 
 
 def _device_ptr(b) -> int:
@@ -238,6 +243,8 @@ def _execute(name: str, plan: Plan, rank_buffers: Sequence, stream) -> None:
         stream = torch.cuda.current_stream().cuda_stream
     elif hasattr(stream, "cuda_stream"):
         stream = stream.cuda_stream
+    if len(rank_buffers) != plan.num_nodes:                # the library reads exactly P pointers
+        raise ValueError(f"{name}: the plan has {plan.num_nodes} ranks, {len(rank_buffers)} buffers were given")
     ptrs = (ctypes.c_void_p * len(rank_buffers))(*[_device_ptr(b) for b in rank_buffers])
     st = getattr(lib(), name)(plan.handle, ptrs, ctypes.c_void_p(int(stream)))
     if st != SCCL_OK:
@@ -260,6 +267,11 @@ def sccl_execute_stepwise(plan: Plan, rank_buffers: Sequence, stream=None) -> No
 def sccl_execute_memcpy(plan: Plan, rank_buffers: Sequence, stream=None) -> None:
     """One device-to-device copy per COPY send (comparator lowering; plans without REDUCE sends only)."""
     _execute("sccl_execute_memcpy", plan, rank_buffers, stream)
+
+
+def sccl_execute_static(plan: Plan, rank_buffers: Sequence, stream=None) -> None:
+    """sccl_execute without any device allocation: the step table goes into the library's static device array."""
+    _execute("sccl_execute_static", plan, rank_buffers, stream)
 
 
 def sccl_plan_stats(plan: Plan) -> dict:

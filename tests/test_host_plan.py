@@ -354,3 +354,31 @@ def test_hostile_sizes_and_enum_values_are_refused_not_trusted():
         assert plan_status(topo, ag, s, "not-a-dtype", 4)[0] == "SCCL_ERR_INVALID_ARG"
     finally:
         del sccl.DTYPE_CODES["not-a-dtype"]
+
+
+def test_static_table_size_is_reported_and_oversized_plans_are_refused_without_a_device():
+    """sccl_execute_static places the step table in a static device array of SCCL_STATIC_SCRATCH_BYTES: the
+    size check comes before any device call, so it can be seen here."""
+    import ctypes as ct
+    topo, ag = tp.ring(4), col.allgather(4, 1)
+    s = gen.greedy_bfs(topo, ag)
+    p = sccl.sccl_plan_create(*__import__("helpers").to_binding(topo, ag, s, "f32", 64),
+                              options={"flags": sccl.SCCL_PLAN_HOST_ONLY, "lowering": sccl.SCCL_LOWER_MEMORY})
+    st = sccl.sccl_plan_stats(p)
+    # chunk offsets (G + 1 words, padded to 4), then header + anchor + others per group
+    groups = st["num_copy_groups"] + st["num_reduce_groups"]
+    assert st["static_table_bytes"] == 4 * (8 + 2 * groups + st["num_sends"])
+    sccl.sccl_plan_destroy(p)
+    # a ring Allgather on 64 ranks with 24 chunks per node: 96 768 sends, a table of about 1 MiB
+    topo, ag = tp.ring(64), col.allgather(64, 24)
+    s = gen.ring_allgather(64, 24)
+    p = sccl.sccl_plan_create(*__import__("helpers").to_binding(topo, ag, s, "f32", 4),
+                              options={"flags": sccl.SCCL_PLAN_HOST_ONLY, "lowering": sccl.SCCL_LOWER_MEMORY})
+    assert sccl.sccl_plan_stats(p)["static_table_bytes"] > sccl.SCCL_STATIC_SCRATCH_BYTES
+    fake = [0x1000 * (n + 1) for n in range(64)]           # never dereferenced: the call must fail before any launch
+    with pytest.raises(sccl.ScclError) as e:
+        sccl.sccl_execute_static(p, fake, stream=0)
+    assert e.value.name == "SCCL_ERR_SCRATCH"
+    with pytest.raises(ValueError):
+        sccl.sccl_execute_static(p, fake[:3], stream=0)
+    sccl.sccl_plan_destroy(p)
