@@ -8,11 +8,14 @@ is launched on; the in-place buffers are restored from a pristine device copy be
 outside the timed windows.
 
 Prints ONE JSON line on stdout.  `--report FILE` additionally times the other configurations and
-writes a markdown table to FILE.
+writes a markdown table to FILE; `--ceilings` prints what plain streaming kernels reach on this GPU.
 """
 import argparse
+import ctypes
+import glob
 import json
 import os
+import re
 import sys
 import time
 
@@ -21,16 +24,119 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+LOWERING_NAMES = {1: "memory", 2: "staged"}
 
-# Bytes that left the L2 per launch, from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each scaled by
-# what the same counter reads for the 1 GiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  Keyed by
-# (workload, grid, block_threads, vectors_per_thread); the figures and commands are in profiles/.
-MEASURED_TRAFFIC = {
-    ("cfg3", 256, 256, 4): (2 * 1097471.0 + 2658935.8) * 1024,
-    ("cfg4", 256, 256, 8): (2 * 2542746.1 + 7158514.2) * 1024,
-    ("cfg2", 256, 256, 8): (2 * 124550.7 + 458752.0) * 1024,
-}
 
+# ---- measurement aids: plain streaming kernels of known traffic (bench_kernels.hip, not part of the library)
+
+_aid = None
+
+
+def bench_kernels():
+    global _aid
+    if _aid is None:
+        path = os.path.join(ROOT, "libbench_kernels.so")
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with __graft_entry__.build()")
+        import torch  # noqa: F401  (one HIP runtime per process: torch's, loaded first)
+        L = ctypes.CDLL(path)
+        L.bench_stream.restype = ctypes.c_int
+        L.bench_stream.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
+                                   ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        _aid = L
+    return _aid
+
+
+STREAM_MODES = {"read": 0, "write": 1, "copy": 2, "fanout": 3, "fanin": 4}
+
+
+def bench_stream(mode, dst, src, nbytes, k=1, grid=1024, sink=None, stream=None):
+    import torch
+    s = (stream or torch.cuda.current_stream()).cuda_stream
+    rc = bench_kernels().bench_stream(STREAM_MODES[mode], ctypes.c_void_p(dst.data_ptr() if dst is not None else 0),
+                                      ctypes.c_void_p(src.data_ptr() if src is not None else 0), ctypes.c_size_t(nbytes),
+                                      int(k), int(grid), ctypes.c_void_p(sink.data_ptr() if sink is not None else 0),
+                                      ctypes.c_void_p(int(s)))
+    if rc != 0:
+        raise RuntimeError(f"bench_stream({mode}) failed with {rc}")
+
+
+def stream_ceilings(part=256 << 20, reps=8, grids=(256, 512, 1024, 2048, 4096)):
+    """GB/s of plain streaming kernels with the executor's access pattern, best grid each: read only, write only,
+    copy, one read fanned out to 7 writes, 8 reads summed into one write.  `part` bytes per region, 8 regions."""
+    import torch
+    a = torch.empty(8 * part, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+    b = torch.empty(8 * part, dtype=torch.uint8, device="cuda:0")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    cases = {"read": ("read", 8 * part, 1, 8 * part), "write": ("write", 8 * part, 1, 8 * part),
+             "copy": ("copy", 8 * part, 1, 16 * part), "fanout_1r_7w": ("fanout", part, 7, 8 * part),
+             "fanin_8r_1w": ("fanin", part, 8, 9 * part)}
+    out = {}
+    for name, (mode, nbytes, k, traffic) in cases.items():
+        best = None
+        for grid in grids:
+            times = []
+            for r in range(reps + 1):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                bench_stream(mode, b, a, nbytes, k, grid, sink)
+                e1.record()
+                torch.cuda.synchronize()
+                if r:
+                    times.append(e0.elapsed_time(e1))
+            med = sorted(times)[len(times) // 2]
+            if best is None or med < best[0]:
+                best = (med, grid)
+        out[name] = {"GBs": round(traffic / (best[0] * 1e-3) / 1e9, 1), "grid": best[1], "ms": round(best[0], 4),
+                     "bytes": traffic}
+    return out
+
+
+# ---- traffic behind the L2, from the committed rocprofv3 summaries under profiles/
+
+def measured_traffic(workload, st):
+    """(bytes per launch, source) from the `traffic:` line of a profile summary whose workload and launch shape match
+    this run's, else (None, None).  The numbers were measured by builder-run `rocprofv3 --pmc` passes (commands in
+    the file), not in this process."""
+    want = {"workload": workload, "lowering": LOWERING_NAMES.get(st["lowering"], "?"), "grid": str(st["grid_workgroups"])}
+    if st["lowering"] == 1:
+        want.update({"block_threads": str(st["block_threads"]), "vectors_per_thread": str(st["vectors_per_thread"])})
+    else:
+        want.update({"slice_vectors": str(st["slice_vectors"]), "staged_threads": str(st["staged_threads"])})
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        with open(path) as f:
+            for line in f:
+                if not line.startswith("traffic:"):
+                    continue
+                kv = dict(re.findall(r"(\w+)=(\S+)", line))
+                if all(kv.get(k) == v for k, v in want.items()) and "fetch_bytes" in kv and "write_bytes" in kv:
+                    return float(kv["fetch_bytes"]) + float(kv["write_bytes"]), f"profiles/{os.path.basename(path)} (builder-run rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)"
+    return None, None
+
+
+def roofline(workload, st, mean_ms):
+    """The roofline object of the JSON line.  `achieved` follows the metric: ALGORITHMIC bytes (every chunk move of
+    the schedule: a copy group reads 1 and writes k chunks, a reduce group reads k + 1 and writes 1) over the
+    kernel's mean duration.  A lane re-reads in step s+1 what it wrote in step s, and those re-reads are served by
+    the L2, so the bytes that actually cross to HBM are fewer: `traffic` (counters), bounded below by
+    `compulsory_bytes` (every cell read before it is written is fetched once, every cell written is written once)."""
+    t = mean_ms * 1e-3
+    gbs = st["bytes_min"] / t / 1e9
+    compulsory = (st["num_cells_loaded"] + st["num_cells_stored"]) * st["chunk_bytes"]
+    traffic, source = measured_traffic(workload, st)
+    r = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+         "traffic": traffic, "traffic_frac": None if traffic is None else round(traffic / t / 1e9 / HBM_PEAK_GBS, 4),
+         "traffic_source": source,
+         "compulsory_bytes": compulsory, "compulsory_frac": round(compulsory / t / 1e9 / HBM_PEAK_GBS, 4),
+         "kernel": ("sccl_staged_kernel" if st["lowering"] == 2 else "sccl_exec_kernel") + " (one launch = the whole schedule)",
+         "kernel_ms": round(mean_ms, 4), "algorithmic_bytes_per_launch": st["bytes_min"],
+         "note": "frac = algorithmic bytes / time / peak, the metric's definition.  It is not a fraction of HBM traffic: "
+                 "re-reads of what a lane wrote one step earlier hit the L2, so frac can exceed traffic_frac (bytes counted "
+                 "behind the L2) and even 1.  compulsory_frac uses only the bytes any execution must move."}
+    return r
+
+
+# ---- running a workload
 
 def make_inputs(wl, sf, device):
     """Pristine device buffers for a workload (seeded, generated on the device; bit-identical to the host recipe
@@ -53,8 +159,22 @@ def make_inputs(wl, sf, device):
     return bufs, epc
 
 
-def time_workload(wl, steps, warmup, options=None, keep=False, mode="sccl_execute"):
-    """Returns dict with per-step kernel times (ms) measured by events on the launch stream."""
+_flush = None
+
+
+def flush_caches():
+    """Overwrites 1 GiB of scratch memory: whatever the L2s (8 x 4 MiB) and the memory-side cache (256 MiB) held of
+    the working set is gone afterwards.  Enqueued on the current stream, outside every timed window."""
+    global _flush
+    import torch
+    if _flush is None:
+        _flush = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    bench_stream("write", _flush, None, 1 << 30, grid=1024)
+
+
+def time_workload(wl, steps, warmup, options=None, keep=False, mode="sccl_execute", cold=False):
+    """Returns dict with per-step kernel times (ms) measured by events on the launch stream.  cold: the caches are
+    flushed between restoring the inputs and the timed launch (else the restore's writes may still sit in them)."""
     import torch
     from paper_2008_08708_amd import schedule_file, sccl
     dev = torch.device("cuda:0")
@@ -69,6 +189,8 @@ def time_workload(wl, steps, warmup, options=None, keep=False, mode="sccl_execut
     def restore():
         for w, p in zip(work, pristine):
             w.copy_(p)
+        if cold:
+            flush_caches()
 
     for _ in range(warmup):
         restore()
@@ -121,27 +243,6 @@ def graph_us_per_execute(wl, count=20, reps=10, options=None):
     return times[len(times) // 2]
 
 
-def copy_ceiling(nbytes, reps=10):
-    """GB/s (read + write) of a plain 16-byte-per-lane copy kernel over nbytes."""
-    import torch
-    from paper_2008_08708_amd import sccl
-    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").random_(0, 255)
-    dst = torch.empty_like(src)
-    stream = torch.cuda.current_stream()
-    for _ in range(2):
-        sccl.sccl_copy_kernel(dst, src, nbytes, stream)
-    evs = []
-    for _ in range(reps):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record(stream)
-        sccl.sccl_copy_kernel(dst, src, nbytes, stream)
-        b.record(stream)
-        evs.append((a, b))
-    torch.cuda.synchronize()
-    ms = sorted(a.elapsed_time(b) for a, b in evs)
-    return 2.0 * nbytes / (ms[len(ms) // 2] * 1e-3) / 1e9
-
-
 def cpu_baseline(run, wl):
     """The oracle, as it stands, on the host cores: the full workload, same plan, same input bits.
     Also compares the GPU's result with it, bit for bit, on the full buffers."""
@@ -151,7 +252,8 @@ def cpu_baseline(run, wl):
     from paper_2008_08708_amd import sccl
     sf, epc = run["sf"], run["epc"]
     sched = osched.Schedule(sf.rounds, sf.sends)
-    threads = min(16, os.cpu_count() or 1, executor.max_threads())
+    nproc = os.cpu_count() or 1
+    threads = max(1, min(nproc, executor.max_threads()))     # every core OpenMP may use (OMP_NUM_THREADS caps it)
     layout = {} if sf.slot is None else {"slot": sf.slot, "slots_per_rank": sf.slots_per_rank}
     host_in = [p.cpu().numpy() for p in run["pristine"]]
     times = []
@@ -177,10 +279,10 @@ def cpu_baseline(run, wl):
     t0 = time.perf_counter()
     executor.execute(wl.dtype, sf.num_chunks, epc, sched, host1, threads=1, **layout)
     one = time.perf_counter() - t0
-    return {"value": run["stats"]["bytes_min"] / med / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+    return {"value": run["stats"]["bytes_min"] / med / 1e9, "unit": "GB/s", "cores": threads, "nproc": nproc, "kind": "oracle",
             "value_one_core": run["stats"]["bytes_min"] / one / 1e9,
             "sample": f"the full workload ({run['stats']['bytes_min'] / 2**30:.2f} GiB algorithmic), median of 3 runs, "
-                      f"OpenMP over the element range"}, same
+                      f"OpenMP over the element range on {threads} threads (the host reports {nproc} processors)"}, same
 
 
 def sweep(wl, steps, warmup):
@@ -190,7 +292,7 @@ def sweep(wl, steps, warmup):
     shapes = [{"lowering": 1, "block_threads": bt, "vectors_per_thread": vt, "max_workgroups": 256 * k}
               for bt in (64, 128, 256) for vt in (1, 2, 4, 8) for k in (1, 2, 4)]
     shapes += [{"lowering": 2, "slice_vectors": sv, "staged_threads": th}
-               for sv in (1, 2, 4, 8, 16, 32, 64, 128) for th in (256, 512, 1024)]
+               for sv in (1, 2, 4, 8, 16, 32, 64, 128) for th in (64, 256, 512, 1024)]
     best = None
     for o in shapes:
         try:
@@ -207,6 +309,125 @@ def sweep(wl, steps, warmup):
     print(json.dumps({"best": best}), flush=True)
 
 
+def report(path, torch, workloads, sccl):
+    """Times every configuration under every lowering, warm and cold, beside the oracle; the torus pair the
+    cost model chooses between; and the streaming ceilings.  Markdown to `path`."""
+    from paper_2008_08708_amd.sccl import SCCL_LOWER_MEMORY, SCCL_LOWER_STAGED, ScclError
+    rows = []
+    names = [(k, workloads.WORKLOADS[k]) for k in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg4b", "alltoall", "broadcast", "reduce",
+                                                   "gather", "scatter")]
+    for coll in ("allgather", "allreduce"):
+        for size in workloads.sweep_sizes():
+            names.append((f"cfg5 {coll} {size}", workloads.sweep_workload(coll, size)))
+
+    def median_us(w, steps, mode, opts=None, cold=False):
+        r = time_workload(w, steps, 3, options=opts, mode=mode, cold=cold)
+        m = sorted(r["ms"])
+        out = (m[len(m) // 2] * 1e3, m[0] * 1e3, r["stats"])
+        del r
+        torch.cuda.empty_cache()
+        return out
+
+    fmt = lambda x: "-" if x is None else format(x, ".1f")
+    for label, w in names:
+        steps = 5 if w.bytes_per_rank >= (1 << 30) else 20
+        med, mn, s = median_us(w, steps, "sccl_execute")                     # the default: lowering chosen by the plan
+        cold_med = median_us(w, steps, "sccl_execute", cold=True)[0]
+        mem_med = med if s["lowering"] == SCCL_LOWER_MEMORY else median_us(w, steps, "sccl_execute", {"lowering": SCCL_LOWER_MEMORY})[0]
+        stg_med = None
+        if s["lowering"] == SCCL_LOWER_STAGED:
+            stg_med = med
+        elif s["staged_available"] and w.bytes_per_rank <= (16 << 20):
+            try:
+                stg_med = median_us(w, steps, "sccl_execute", {"lowering": SCCL_LOWER_STAGED})[0]
+            except ScclError:
+                stg_med = None
+        graph_us = graph_us_per_execute(w) if w.bytes_per_rank <= (1 << 20) else None
+        oracle = None                                    # (GB/s on the host cores, GB/s on one core, cores, bitwise equal)
+        if s["num_nodes"] * w.bytes_per_rank <= (4 << 30):
+            kept = time_workload(w, 1, 0, keep=True)
+            base, same = cpu_baseline(kept, w)
+            oracle = (base["value"], base["value_one_core"], base["cores"], same)
+            sccl.sccl_plan_destroy(kept["plan"])
+            del kept
+            torch.cuda.empty_cache()
+        step_med, _, _ = median_us(w, steps, "sccl_execute_stepwise")
+        cpy_med = median_us(w, steps, "sccl_execute_memcpy")[0] if s["num_reduce_groups"] == 0 else None
+        rf = roofline(w.name, s, med * 1e-3)
+        rows.append((label, s["num_nodes"], w.bytes_per_rank, s["chunk_bytes"], s["num_steps"], s["bytes_min"],
+                     med, mn, s["bytes_min"] / (med * 1e-6) / 1e9, "staged" if s["lowering"] == SCCL_LOWER_STAGED else "memory",
+                     s["num_levels"], s["grid_workgroups"], mem_med, stg_med, step_med, cpy_med, graph_us, oracle, cold_med, rf))
+        print(f"[report] {label}: default ({rows[-1][9]}) {med:.1f} us warm, {cold_med:.1f} us cold ({rows[-1][8]:.1f} GB/s), "
+              f"through memory {fmt(mem_med)} us, staged {fmt(stg_med)} us, per-step kernels {fmt(step_med)} us, "
+              f"per-send copies {fmt(cpy_med)} us, in a graph of 20 {fmt(graph_us)} us each", file=sys.stderr, flush=True)
+    os.makedirs(os.path.dirname(os.path.abspath(path)), exist_ok=True)
+    with open(path, "w") as f:
+        f.write("| workload | P | bytes/rank | chunk bytes | S | bytes_min | sccl_execute: median us | min us | cold caches: median us "
+                "| effective GB/s | algorithmic % of 8 TB/s | compulsory % of 8 TB/s "
+                "| lowering | levels | grid | through memory: us | staged: us | one kernel per step: us | one copy per send: us "
+                "| each of 20 in one HIP graph: us | oracle on the host cores: GB/s (cores) | oracle on one core: GB/s "
+                "| full buffers bitwise equal to the oracle's |\n")
+        f.write("|" + "---|" * 23 + "\n")
+        for r in rows:
+            f.write(f"| {r[0]} | {r[1]} | {r[2]} | {r[3]} | {r[4]} | {r[5]} | {r[6]:.1f} | {r[7]:.1f} | {r[18]:.1f} | {r[8]:.1f} | "
+                    f"{100 * r[19]['frac']:.1f} | {100 * r[19]['compulsory_frac']:.1f} | {r[9]} | {r[10]} | {r[11]} | {fmt(r[12])} | {fmt(r[13])} | "
+                    f"{fmt(r[14])} | {fmt(r[15])} | {fmt(r[16])} | "
+                    + ("- | - | (every byte: tests/test_gpu_fullsize.py) |\n" if r[17] is None else
+                       f"{r[17][0]:.1f} ({r[17][2]}) | {r[17][1]:.1f} | {'yes' if r[17][3] else 'NO'} |\n"))
+    # ---- the paper's size-dependent choice between two algorithms (section 5.5) on this hardware: the
+    # latency-optimal and the bandwidth-optimal torus algorithm at every size, and what two fits of the cost model
+    # would have chosen: the paper's t = S alpha + (R/C) L beta, and the same with a launch intercept t0.
+    with open(path, "a") as f:
+        f.write("\n| collective | bytes/rank | latency-optimal: us | bandwidth-optimal: us | measured best | paper's model chooses "
+                "| model with intercept chooses |\n|---|---|---|---|---|---|---|\n")
+        score = {"paper": 0, "intercept": 0, "rows": 0}
+        for coll in ("allgather", "allreduce"):
+            meas = []
+            for size in workloads.sweep_sizes():
+                pair = []
+                for alg in ("latency", "bandwidth"):
+                    w = workloads.sweep_workload(coll, size, alg)
+                    steps = 5 if size >= (1 << 30) else 20
+                    med, _, st_ = median_us(w, steps, "sccl_execute")
+                    # the model's two coordinates: a = S, b = (R / C) * L = R * chunk bytes
+                    pair.append((med * 1e-6, float(st_["num_steps"]), float(st_["num_rounds"]) * st_["chunk_bytes"]))
+                meas.append((size, pair))
+            a = [p[1] for _, pair in meas for p in pair]
+            b = [p[2] for _, pair in meas for p in pair]
+            t = [p[0] for _, pair in meas for p in pair]
+            alpha, beta = sccl.sccl_cost_fit(a, b, t)
+            t0, alpha3, beta3 = sccl.sccl_cost_fit_intercept(a, b, t)
+            for size, pair in meas:
+                model = [p[1] * alpha + p[2] * beta for p in pair]
+                model3 = [t0 + p[1] * alpha3 + p[2] * beta3 for p in pair]
+                best = "latency" if pair[0][0] <= pair[1][0] else "bandwidth"
+                c2 = "latency" if model[0] <= model[1] else "bandwidth"
+                c3 = "latency" if model3[0] <= model3[1] else "bandwidth"
+                score["rows"] += 1
+                score["paper"] += c2 == best
+                score["intercept"] += c3 == best
+                f.write(f"| {coll} | {size} | {pair[0][0] * 1e6:.1f} | {pair[1][0] * 1e6:.1f} | {best} | {c2} | {c3} |\n")
+            f.write(f"\n{coll}: paper's model alpha = {alpha * 1e6:.3f} us per step, 1 / beta = "
+                    f"{1e-9 / beta if beta > 0 else float('inf'):.0f} GB/s; with intercept t0 = {t0 * 1e6:.2f} us, alpha = "
+                    f"{alpha3 * 1e6:.3f} us per step, 1 / beta = {1e-9 / beta3 if beta3 > 0 else float('inf'):.0f} GB/s\n")
+            print(f"[report] {coll}: alpha {alpha * 1e6:.3f} us, beta {beta * 1e12:.4f} ps/B; with intercept t0 {t0 * 1e6:.2f} us, "
+                  f"alpha {alpha3 * 1e6:.3f} us, beta {beta3 * 1e12:.4f} ps/B", file=sys.stderr, flush=True)
+        f.write(f"\nRight choices out of {score['rows']}: the paper's model {score['paper']}, the model with a launch intercept "
+                f"{score['intercept']}.\n")
+        ceil = stream_ceilings()
+        f.write("\n| plain streaming kernel (256 MiB regions) | GB/s | % of 8 TB/s | best grid |\n|---|---|---|---|\n")
+        for k, v in ceil.items():
+            f.write(f"| {k} | {v['GBs']:.0f} | {100 * v['GBs'] / HBM_PEAK_GBS:.1f} | {v['grid']} |\n")
+        f.write("\nContext, not a target: the paper gives no absolute time or bandwidth for executing a schedule in its "
+                "text, only speedups measured across eight GPUs over their links (section 5.5): Allgather up to 2.2x "
+                "(small) and 1.14x (large) over NCCL 2.7.8, Allreduce up to 1.8x (small, the 8-chunk algorithm) and 1.06x "
+                "(large, the 48-chunk algorithm), Alltoall more than 6.8x (large) over point-to-point copies, on a DGX-1 "
+                "(8 x V100, six 25 GB/s NVLink ports per GPU); Allgather faster than RCCL only at large sizes on a Gigabyte "
+                "Z52 (8 x MI50, xGMI about 33 GB/s, PCIe 4 about 27 GB/s).  Nothing here reproduces an inter-GPU link: the "
+                "figures above are one MI355X moving P virtual ranks' buffers inside its own HBM "
+                f"(peak {HBM_PEAK_GBS / 1000:.0f} TB/s).\n")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -217,7 +438,13 @@ def main():
     ap.add_argument("--vectors-per-thread", type=int, default=0)
     ap.add_argument("--max-workgroups", type=int, default=0)
     ap.add_argument("--lowering", type=int, default=0, help="0 = the plan chooses, 1 = through memory, 2 = staged in the local data share")
+    ap.add_argument("--slice-vectors", type=int, default=0)
+    ap.add_argument("--staged-threads", type=int, default=0)
+    ap.add_argument("--cold", action="store_true",
+                    help="flush the caches (a 1 GiB scratch write) between restoring the inputs and every timed launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the plain streaming kernels")
+    ap.add_argument("--ceilings", action="store_true", help="only measure the plain streaming kernels; one JSON line")
     ap.add_argument("--report", default="", metavar="FILE", help="also time the other configurations; markdown table to FILE")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: time --workload under every launch shape of both kernels "
@@ -235,17 +462,21 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.ceilings:
+        print(json.dumps({"streaming_ceilings": stream_ceilings(), "peak_GBs": HBM_PEAK_GBS}), flush=True)
+        return
     options = {k: v for k, v in (("block_threads", args.block_threads), ("vectors_per_thread", args.vectors_per_thread),
-                                 ("max_workgroups", args.max_workgroups), ("lowering", args.lowering)) if v}
-    if args.workload.startswith("cfg5:"):             # cfg5:<allgather|allreduce>:<bytes per rank>
-        _, coll_name, size = args.workload.split(":")
-        wl = workloads.sweep_workload(coll_name, int(size))
+                                 ("max_workgroups", args.max_workgroups), ("lowering", args.lowering),
+                                 ("slice_vectors", args.slice_vectors), ("staged_threads", args.staged_threads)) if v}
+    if args.workload.startswith("cfg5:"):             # cfg5:<allgather|allreduce>:<bytes per rank>[:latency]
+        parts = args.workload.split(":")
+        wl = workloads.sweep_workload(parts[1], int(parts[2]), parts[3] if len(parts) > 3 else "bandwidth")
     else:
         wl = workloads.WORKLOADS[args.workload]
     if args.sweep:
         sweep(wl, args.steps, args.warmup)
         return
-    run = time_workload(wl, args.steps, args.warmup, options or None, keep=True)
+    run = time_workload(wl, args.steps, args.warmup, options or None, keep=True, cold=args.cold)
     st = run["stats"]
     ms = run["ms"]
     mean_ms = sum(ms) / len(ms)
@@ -260,23 +491,37 @@ def main():
                                f"{wl.bytes_per_rank >> 20} MiB {wl.dtype}, G={st['num_global_chunks']} chunks, "
                                f"S={st['num_steps']} steps, {st['num_sends']} sends",
                    "bytes_min": st["bytes_min"], "bytes_unfused": st["bytes_unfused"],
-                   "grid": st["grid_workgroups"], "block_threads": st["block_threads"],
-                   "vectors_per_thread": st["vectors_per_thread"]},
+                   "lowering": LOWERING_NAMES.get(st["lowering"]), "grid": st["grid_workgroups"],
+                   "block_threads": st["block_threads"], "vectors_per_thread": st["vectors_per_thread"],
+                   "caches": "flushed before every timed launch" if args.cold else "as the restore of the inputs left them"},
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "ms_min": round(min(ms), 4), "ms_median": round(sorted(ms)[len(ms) // 2], 4),
         "wall_ms_per_step_incl_restore": round(run["wall_s"] * 1e3 / args.steps, 4),
-        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC.get((args.workload, st["grid_workgroups"], st["block_threads"],
-                                                      st["vectors_per_thread"])),
-                     "kernel": ("sccl_staged_kernel" if st["lowering"] == 2 else "sccl_exec_kernel") + " (one launch = the whole schedule)",
-                     "algorithmic_bytes_per_launch": st["bytes_min"]},
+        "roofline": roofline(wl.name, st, mean_ms),
     }
-    try:
-        line["copy_kernel_ceiling_gbs"] = round(copy_ceiling(1 << 30), 1)
-    except Exception as e:                        # measurement aid only
-        line["copy_kernel_ceiling_gbs"] = None
-        print(f"copy ceiling failed: {e}", file=sys.stderr)
+    if not args.cold and not args.no_ceilings:
+        # the same kernel with cold caches (untimed region: restore + 1 GiB scratch write), a few steps
+        for w, p in zip(run["work"], run["pristine"]):
+            w.copy_(p)
+        cold = []
+        for _ in range(min(5, args.steps)):
+            for w, p in zip(run["work"], run["pristine"]):
+                w.copy_(p)
+            flush_caches()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            sccl.sccl_execute(run["plan"], run["work"])
+            b.record()
+            torch.cuda.synchronize()
+            cold.append(a.elapsed_time(b))
+        line["ms_per_step_cold_caches"] = round(sum(cold) / len(cold), 4)
+    if not args.no_ceilings:
+        try:
+            c = stream_ceilings(reps=4, grids=(1024, 2048))
+            line["streaming_ceilings_gbs"] = {k: v["GBs"] for k, v in c.items()}
+        except Exception as e:                    # measurement aid only
+            line["streaming_ceilings_gbs"] = None
+            print(f"streaming ceilings failed: {e}", file=sys.stderr)
     if not args.no_cpu_baseline:
         base, same = cpu_baseline(run, wl)
         line["cpu_baseline"] = base
@@ -284,109 +529,8 @@ def main():
     sccl.sccl_plan_destroy(run["plan"])
     del run
     torch.cuda.empty_cache()
-
     if args.report:
-        rows = []
-        names = [("cfg1", workloads.WORKLOADS["cfg1"]), ("cfg2", workloads.WORKLOADS["cfg2"]),
-                 ("cfg3", workloads.WORKLOADS["cfg3"]), ("cfg4", workloads.WORKLOADS["cfg4"]),
-                 ("cfg4b", workloads.WORKLOADS["cfg4b"])]
-        names += [(k, workloads.WORKLOADS[k]) for k in ("alltoall", "broadcast", "reduce", "gather", "scatter")]
-        for coll in ("allgather", "allreduce"):
-            for size in workloads.sweep_sizes():
-                names.append((f"cfg5 {coll} {size}", workloads.sweep_workload(coll, size)))
-        from paper_2008_08708_amd.sccl import SCCL_LOWER_MEMORY, SCCL_LOWER_STAGED, ScclError
-
-        def median_us(w, steps, mode, opts=None):
-            r = time_workload(w, steps, 3, options=opts, mode=mode)
-            m = sorted(r["ms"])
-            out = (m[len(m) // 2] * 1e3, m[0] * 1e3, r["stats"])
-            del r
-            torch.cuda.empty_cache()
-            return out
-
-        for label, w in names:
-            steps = 5 if w.bytes_per_rank >= (1 << 30) else 20
-            med, mn, s = median_us(w, steps, "sccl_execute")                     # the default: lowering chosen by the plan
-            mem_med = med if s["lowering"] == SCCL_LOWER_MEMORY else median_us(w, steps, "sccl_execute", {"lowering": SCCL_LOWER_MEMORY})[0]
-            stg_med = None
-            if s["lowering"] == SCCL_LOWER_STAGED:
-                stg_med = med
-            elif s["staged_available"] and w.bytes_per_rank <= (16 << 20):
-                try:
-                    stg_med = median_us(w, steps, "sccl_execute", {"lowering": SCCL_LOWER_STAGED})[0]
-                except ScclError:
-                    stg_med = None
-            graph_us = graph_us_per_execute(w) if w.bytes_per_rank <= (1 << 20) else None
-            oracle = None                                    # (GB/s on the host cores, GB/s on one core, cores, bitwise equal)
-            if s["num_nodes"] * w.bytes_per_rank <= (4 << 30):
-                kept = time_workload(w, 1, 0, keep=True)
-                base, same = cpu_baseline(kept, w)
-                oracle = (base["value"], base["value_one_core"], base["cores"], same)
-                sccl.sccl_plan_destroy(kept["plan"])
-                del kept
-                torch.cuda.empty_cache()
-            step_med, _, _ = median_us(w, steps, "sccl_execute_stepwise")
-            cpy_med = median_us(w, steps, "sccl_execute_memcpy")[0] if s["num_reduce_groups"] == 0 else None
-            rows.append((label, s["num_nodes"], w.bytes_per_rank, s["chunk_bytes"], s["num_steps"], s["bytes_min"],
-                         med, mn, s["bytes_min"] / (med * 1e-6) / 1e9, "staged" if s["lowering"] == SCCL_LOWER_STAGED else "memory",
-                         s["num_levels"], s["grid_workgroups"], mem_med, stg_med, step_med, cpy_med, graph_us, oracle))
-            fmt = lambda x: "-" if x is None else format(x, ".1f")
-            print(f"[report] {label}: default ({rows[-1][9]}) {med:.1f} us ({rows[-1][8]:.1f} GB/s), through memory {fmt(mem_med)} us, "
-                  f"staged {fmt(stg_med)} us, per-step kernels {fmt(step_med)} us, per-send copies {fmt(cpy_med)} us, "
-                  f"in a graph of 20 {fmt(graph_us)} us each",
-                  file=sys.stderr, flush=True)
-        os.makedirs(os.path.dirname(os.path.abspath(args.report)), exist_ok=True)
-        with open(args.report, "w") as f:
-            f.write("| workload | P | bytes/rank | chunk bytes | S | bytes_min | sccl_execute: median us | min us | effective GB/s | % of 8 TB/s "
-                    "| lowering | levels | grid | through memory: us | staged: us | one kernel per step: us | one copy per send: us "
-                    "| each of 20 in one HIP graph: us | oracle on the host cores: GB/s (cores) | oracle on one core: GB/s "
-                    "| full buffers bitwise equal to the oracle's |\n")
-            f.write("|" + "---|" * 21 + "\n")
-            fmt = lambda x: "-" if x is None else format(x, ".1f")
-            for r in rows:
-                f.write(f"| {r[0]} | {r[1]} | {r[2]} | {r[3]} | {r[4]} | {r[5]} | {r[6]:.1f} | {r[7]:.1f} | {r[8]:.1f} | "
-                        f"{100 * r[8] / HBM_PEAK_GBS:.1f} | {r[9]} | {r[10]} | {r[11]} | {fmt(r[12])} | {fmt(r[13])} | "
-                        f"{fmt(r[14])} | {fmt(r[15])} | {fmt(r[16])} | "
-                        + ("- | - | (sampled windows: tests/test_gpu_fullsize.py) |\n" if r[17] is None else
-                           f"{r[17][0]:.1f} ({r[17][2]}) | {r[17][1]:.1f} | {'yes' if r[17][3] else 'NO'} |\n"))
-        # ---- the paper's size-dependent choice between two algorithms (section 5.5) on this hardware: the
-        # latency-optimal and the bandwidth-optimal torus algorithm at every size, the (alpha, beta) of the cost
-        # model fitted to the measurements, and what the model would have chosen.
-        with open(args.report, "a") as f:
-            f.write("\n| collective | bytes/rank | latency-optimal: us | bandwidth-optimal: us | measured best | model's choice "
-                    "| model us (latency / bandwidth) |\n|---|---|---|---|---|---|---|\n")
-            for coll in ("allgather", "allreduce"):
-                meas = []
-                for size in workloads.sweep_sizes():
-                    pair = []
-                    for alg in ("latency", "bandwidth"):
-                        w = workloads.sweep_workload(coll, size, alg)
-                        steps = 5 if size >= (1 << 30) else 20
-                        med, _, st_ = median_us(w, steps, "sccl_execute")
-                        # the model's two coordinates: a = S, b = (R / C) * L = R * chunk bytes
-                        pair.append((med * 1e-6, float(st_["num_steps"]), float(st_["num_rounds"]) * st_["chunk_bytes"]))
-                    meas.append((size, pair))
-                a = [p[1] for _, pair in meas for p in pair]
-                b = [p[2] for _, pair in meas for p in pair]
-                t = [p[0] for _, pair in meas for p in pair]
-                alpha, beta = sccl.sccl_cost_fit(a, b, t)
-                for size, pair in meas:
-                    model = [p[1] * alpha + p[2] * beta for p in pair]
-                    f.write(f"| {coll} | {size} | {pair[0][0] * 1e6:.1f} | {pair[1][0] * 1e6:.1f} | "
-                            f"{'latency' if pair[0][0] <= pair[1][0] else 'bandwidth'} | "
-                            f"{'latency' if model[0] <= model[1] else 'bandwidth'} | {model[0] * 1e6:.1f} / {model[1] * 1e6:.1f} |\n")
-                f.write(f"\n{coll}: fitted alpha = {alpha * 1e6:.3f} us per step, beta = {beta * 1e12:.4f} ps per byte "
-                        f"(1 / beta = {1e-9 / beta if beta > 0 else float('inf'):.0f} GB/s per link-equivalent)\n")
-                print(f"[report] {coll}: alpha {alpha * 1e6:.3f} us, beta {beta * 1e12:.4f} ps/B", file=sys.stderr, flush=True)
-        with open(args.report, "a") as f:
-            f.write("\nContext, not a target: the paper gives no absolute time or bandwidth for executing a schedule in its "
-                    "text, only speedups measured across eight GPUs over their links (section 5.5): Allgather up to 2.2x "
-                    "(small) and 1.14x (large) over NCCL 2.7.8, Allreduce up to 1.8x (small, the 8-chunk algorithm) and 1.06x "
-                    "(large, the 48-chunk algorithm), Alltoall more than 6.8x (large) over point-to-point copies, on a DGX-1 "
-                    "(8 x V100, six 25 GB/s NVLink ports per GPU); Allgather faster than RCCL only at large sizes on a Gigabyte "
-                    "Z52 (8 x MI50, xGMI about 33 GB/s, PCIe 4 about 27 GB/s).  Nothing here reproduces an inter-GPU link: the "
-                    "figures above are one MI355X moving P virtual ranks' buffers inside its own HBM "
-                    f"(peak {HBM_PEAK_GBS / 1000:.0f} TB/s).\n")
+        report(args.report, torch, workloads, sccl)
     print(json.dumps(line), flush=True)
 
 

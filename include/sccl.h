@@ -298,13 +298,14 @@ sccl_status_t sccl_cost_fit(int32_t n, const double* a, const double* b, const d
                             double* out_beta);
 
 /*
- * Measurement aid, not part of the method: a plain 16-byte-per-lane copy
- * kernel dst[i] = src[i] over `bytes` bytes (a multiple of 16, both pointers
- * 16-byte aligned device memory), enqueued on `stream`.  Used to measure the
- * achievable copy bandwidth on the same buffers and to calibrate hardware
- * byte counters against a known traffic volume.
+ * The same fit with a constant term: least squares for t = t0 + a * alpha + b * beta, n >= 3.  On one GPU a
+ * launch costs a few microseconds whatever the schedule, which the paper's two-term model (section 3.6) has no
+ * place for; with t0 taken out, alpha and beta describe what a step and a byte add.  t0 does not change which of
+ * several plans sccl_select_plan prefers; the alpha and beta fitted beside it do.  SCCL_ERR_INVALID_ARG if the
+ * samples do not determine the three constants.
  */
-sccl_status_t sccl_copy_kernel(void* dst, const void* src, size_t bytes, void* stream);
+sccl_status_t sccl_cost_fit_intercept(int32_t n, const double* a, const double* b, const double* t, double* out_t0,
+                                      double* out_alpha, double* out_beta);
 
 #ifdef __cplusplus
 }

@@ -34,11 +34,13 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
-def build_probe(verbose: bool = False) -> str:
-    """Compile the standalone bandwidth probe (a measurement aid) next to the library."""
-    out = os.path.join(HERE, "bw_probe")
-    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           os.path.join(HERE, "csrc", "bw_probe.hip"), "-o", out]
+def build_bench_kernels(verbose: bool = False) -> str:
+    """Compile bench.py's measurement aids (plain streaming kernels of known traffic) into libbench_kernels.so
+    beside bench.py.  They are not part of the library."""
+    out = os.path.join(ROOT, "libbench_kernels.so")
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-x", "hip", os.path.join(ROOT, "bench_kernels.hip"), "-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
@@ -54,4 +56,4 @@ def is_stale() -> bool:
 
 if __name__ == "__main__":
     print(build_library(verbose=True))
-    print(build_probe(verbose=True))
+    print(build_bench_kernels(verbose=True))

@@ -1,6 +1,7 @@
 // The paper's (alpha, beta) cost model on the library side (section 3.6) and what it is used for there
 // (section 5.5): choosing, per input size, among several algorithms for the same collective.  Host only.
 #include <cmath>
+#include <utility>
 
 #include "plan.hpp"
 
@@ -45,6 +46,43 @@ sccl_status_t sccl_cost_fit(int32_t n, const double* a, const double* b, const d
     if (!(std::fabs(det) > 1e-300 * (saa * sbb + 1e-300)) || !std::isfinite(det)) return SCCL_ERR_INVALID_ARG;   // collinear samples
     *out_alpha = (sat * sbb - sbt * sab) / det;
     *out_beta = (saa * sbt - sab * sat) / det;
+    return SCCL_OK;
+}
+
+// Least squares for t_i = t0 + a_i * alpha + b_i * beta.  The three columns differ by many orders of magnitude
+// (1, steps, bytes), so each is scaled by its largest magnitude before the 3 x 3 normal equations are solved
+// by elimination with partial pivoting.
+sccl_status_t sccl_cost_fit_intercept(int32_t n, const double* a, const double* b, const double* t, double* out_t0,
+                                      double* out_alpha, double* out_beta) {
+    if (n < 3 || !a || !b || !t || !out_t0 || !out_alpha || !out_beta) return SCCL_ERR_INVALID_ARG;
+    double sa = 0, sb = 0;
+    for (int32_t i = 0; i < n; i++) {
+        if (!std::isfinite(a[i]) || !std::isfinite(b[i]) || !std::isfinite(t[i])) return SCCL_ERR_INVALID_ARG;
+        sa = std::fmax(sa, std::fabs(a[i])); sb = std::fmax(sb, std::fabs(b[i]));
+    }
+    if (!(sa > 0) || !(sb > 0)) return SCCL_ERR_INVALID_ARG;
+    double m[3][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+    for (int32_t i = 0; i < n; i++) {
+        const double x[3] = {1.0, a[i] / sa, b[i] / sb};
+        for (int r = 0; r < 3; r++) {
+            for (int c = 0; c < 3; c++) m[r][c] += x[r] * x[c];
+            m[r][3] += x[r] * t[i];
+        }
+    }
+    for (int col = 0; col < 3; col++) {
+        int piv = col;
+        for (int r = col + 1; r < 3; r++) if (std::fabs(m[r][col]) > std::fabs(m[piv][col])) piv = r;
+        if (!(std::fabs(m[piv][col]) > 1e-12 * (double)n)) return SCCL_ERR_INVALID_ARG;     // the columns are dependent
+        for (int c = 0; c < 4; c++) std::swap(m[col][c], m[piv][c]);
+        for (int r = 0; r < 3; r++) {
+            if (r == col) continue;
+            const double f = m[r][col] / m[col][col];
+            for (int c = col; c < 4; c++) m[r][c] -= f * m[col][c];
+        }
+    }
+    *out_t0 = m[0][3] / m[0][0];
+    *out_alpha = m[1][3] / m[1][1] / sa;
+    *out_beta = m[2][3] / m[2][2] / sb;
     return SCCL_OK;
 }
 

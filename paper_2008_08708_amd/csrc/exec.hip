@@ -313,23 +313,6 @@ __global__ void __launch_bounds__(256) sccl_step_kernel(const StepArgs a) {
     }
 }
 
-// Plain copy: every lane keeps 8 independent 16-byte loads in flight, then stores them; tiles of
-// 256 lanes x 8 vectors are handed out grid-stride.  The tail (< one tile) is copied vector by vector.
-__global__ void __launch_bounds__(256) copy16_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n) {
-    constexpr size_t U = 8;
-    const size_t tile = 256 * U;
-    const size_t full = n / tile;
-    for (size_t t = blockIdx.x; t < full; t += gridDim.x) {
-        const size_t base = t * tile + threadIdx.x;
-        u32x4 x[U];
-#pragma unroll
-        for (size_t u = 0; u < U; u++) x[u] = src[base + u * 256];
-#pragma unroll
-        for (size_t u = 0; u < U; u++) dst[base + u * 256] = x[u];
-    }
-    for (size_t i = full * tile + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
-}
-
 
 // ---- the staged lowering -----------------------------------------------------------------------
 // A work item is (chunk, slice): `slice` consecutive vectors of the chunk, in every rank buffer that holds
@@ -934,21 +917,6 @@ const char* sccl_status_string(sccl_status_t status) {
         case SCCL_ERR_SCRATCH: return "SCCL_ERR_SCRATCH";
     }
     return "SCCL_ERR_UNKNOWN";
-}
-
-sccl_status_t sccl_copy_kernel(void* dst, const void* src, size_t bytes, void* stream) {
-    if (!dst || !src || (bytes & 15u) || ((uintptr_t)dst & 15u) || ((uintptr_t)src & 15u)) return SCCL_ERR_INVALID_ARG;
-    if (bytes == 0) return SCCL_OK;
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return SCCL_ERR_DEVICE;
-    const size_t n = bytes / 16;
-    size_t grid = (n + 2047) / 2048;
-    const size_t cap = (size_t)cus * 4;
-    if (grid > cap) grid = cap;
-    hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream,
-                       (u32x4*)dst, (const u32x4*)src, n);
-    return hipGetLastError() == hipSuccess ? SCCL_OK : SCCL_ERR_DEVICE;
 }
 
 }  // extern "C"

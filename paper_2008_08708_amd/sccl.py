@@ -87,7 +87,7 @@ class sccl_stats_t(ctypes.Structure):
 
 EXPORTS = ["sccl_plan_create", "sccl_plan_create_ex", "sccl_execute", "sccl_execute_stepwise", "sccl_execute_memcpy",
            "sccl_execute_static", "sccl_plan_stats", "sccl_plan_destroy",
-           "sccl_status_string", "sccl_copy_kernel", "sccl_plan_cost", "sccl_select_plan", "sccl_cost_fit"]
+           "sccl_status_string", "sccl_plan_cost", "sccl_select_plan", "sccl_cost_fit", "sccl_cost_fit_intercept"]
 
 _lib = None
 
@@ -122,8 +122,6 @@ def lib() -> ctypes.CDLL:
         L.sccl_plan_destroy.argtypes = [ctypes.c_void_p]
         L.sccl_status_string.restype = ctypes.c_char_p
         L.sccl_status_string.argtypes = [ctypes.c_int]
-        L.sccl_copy_kernel.restype = ctypes.c_int
-        L.sccl_copy_kernel.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.sccl_plan_cost.restype = ctypes.c_int
         L.sccl_plan_cost.argtypes = [ctypes.c_void_p, ctypes.c_double, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
         L.sccl_select_plan.restype = ctypes.c_int
@@ -132,6 +130,10 @@ def lib() -> ctypes.CDLL:
         L.sccl_cost_fit.restype = ctypes.c_int
         L.sccl_cost_fit.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                     ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+        L.sccl_cost_fit_intercept.restype = ctypes.c_int
+        L.sccl_cost_fit_intercept.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                              ctypes.POINTER(ctypes.c_double)]
         _lib = L
     return _lib
 
@@ -288,18 +290,6 @@ def sccl_plan_destroy(plan: Plan) -> None:
         plan.handle = ctypes.c_void_p()
 
 
-def sccl_copy_kernel(dst, src, nbytes: int, stream=None) -> None:
-    if stream is None:
-        import torch
-        stream = torch.cuda.current_stream().cuda_stream
-    elif hasattr(stream, "cuda_stream"):
-        stream = stream.cuda_stream
-    st = lib().sccl_copy_kernel(ctypes.c_void_p(_device_ptr(dst)), ctypes.c_void_p(_device_ptr(src)),
-                                ctypes.c_size_t(int(nbytes)), ctypes.c_void_p(int(stream)))
-    if st != SCCL_OK:
-        raise ScclError(st, "sccl_copy_kernel")
-
-
 def sccl_plan_cost(plan: Plan, alpha: float, beta: float) -> float:
     """Seconds the paper's (alpha, beta) model gives the plan."""
     out = ctypes.c_double()
@@ -329,3 +319,16 @@ def sccl_cost_fit(a: Sequence[float], b: Sequence[float], t: Sequence[float]) ->
     if st != SCCL_OK:
         raise ScclError(st, "sccl_cost_fit")
     return al.value, be.value
+
+
+def sccl_cost_fit_intercept(a: Sequence[float], b: Sequence[float], t: Sequence[float]) -> Tuple[float, float, float]:
+    """(t0, alpha, beta) of the least-squares fit t = t0 + a * alpha + b * beta."""
+    aa, bb, tt = (np.ascontiguousarray(x, dtype=np.float64) for x in (a, b, t))
+    if not (aa.shape == bb.shape == tt.shape and aa.ndim == 1):
+        raise ValueError("a, b, t must be 1-d arrays of one length")
+    t0, al, be = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    st = lib().sccl_cost_fit_intercept(aa.size, aa.ctypes.data, bb.ctypes.data, tt.ctypes.data, ctypes.byref(t0),
+                                       ctypes.byref(al), ctypes.byref(be))
+    if st != SCCL_OK:
+        raise ScclError(st, "sccl_cost_fit_intercept")
+    return t0.value, al.value, be.value

@@ -226,14 +226,23 @@ def test_device_generator_matches_host_generator():
         assert (bits(a) == bits(b)).all()
 
 
-def test_copy_kernel():
+def test_streaming_kernels_of_the_benchmark_move_what_they_say():
+    # bench.py's measurement aids (not part of the library): a copy is a copy, a fan-out writes k copies, a fan-in sums
     import torch
-    for n in ((1 << 20) + 4 * 37, 4 * 5, 8192 * 3):          # whole tiles plus a tail; a tail only; tiles only
-        src = torch.arange(n, dtype=torch.int32, device="cuda")
-        dst = torch.zeros_like(src)
-        sccl.sccl_copy_kernel(dst, src, n * 4)
-        torch.cuda.synchronize()
-        assert torch.equal(src, dst)
+    import bench
+    n = 3 * 32768                                           # bytes per region: three tiles
+    src = torch.randint(0, 1 << 30, (8 * n // 4,), dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    bench.bench_stream("copy", dst, src, 8 * n, grid=2)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    dst.zero_()
+    bench.bench_stream("fanout", dst, src, n, k=7, grid=5)
+    torch.cuda.synchronize()
+    assert torch.equal(dst.view(8, -1)[:7], src.view(8, -1)[:1].expand(7, -1)) and not dst.view(8, -1)[7].any()
+    bench.bench_stream("fanin", dst, src, n, k=8, grid=3)
+    torch.cuda.synchronize()
+    assert torch.equal(dst.view(8, -1)[0], src.view(8, -1).sum(0, dtype=torch.int32))
 
 
 def test_synthesized_schedules_with_several_rounds_per_step():

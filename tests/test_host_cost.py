@@ -118,3 +118,27 @@ def test_fit_recovers_the_constants_and_matches_numpy():
         sccl.sccl_cost_fit([1.0, 2.0, 3.0], [2.0, 4.0, 6.0], [1.0, 2.0, 3.0])
     with pytest.raises(sccl.ScclError):
         sccl.sccl_cost_fit([1.0], [2.0], [1.0])
+
+
+def test_fit_with_an_intercept_recovers_the_constants_and_matches_numpy():
+    rng = np.random.default_rng(11)
+    t0, alpha, beta = 5.1e-6, 0.45e-6, 1.0 / 6e12
+    a = rng.integers(2, 31, size=44).astype(np.float64)
+    b = 10.0 ** rng.uniform(1, 10.5, size=44)              # 16 bytes ... tens of gigabytes: the range of the size sweep
+    t = t0 + a * alpha + b * beta
+    g0, ga, gb = sccl.sccl_cost_fit_intercept(a, b, t)
+    assert g0 == pytest.approx(t0, rel=1e-7) and ga == pytest.approx(alpha, rel=1e-7) and gb == pytest.approx(beta, rel=1e-7)
+    noisy = t * (1 + 0.05 * rng.standard_normal(44))
+    g0, ga, gb = sccl.sccl_cost_fit_intercept(a, b, noisy)
+    A = np.stack([np.ones_like(a), a / a.max(), b / b.max()], axis=1)     # numpy's least squares, on scaled columns
+    ref = np.linalg.lstsq(A, noisy, rcond=None)[0]
+    assert g0 == pytest.approx(ref[0], rel=1e-6)
+    assert ga == pytest.approx(ref[1] / a.max(), rel=1e-6) and gb == pytest.approx(ref[2] / b.max(), rel=1e-6)
+    # with t0 = 0 in the data the two fits agree on alpha and beta
+    al2, be2 = sccl.sccl_cost_fit(a, b, a * alpha + b * beta)
+    z0, al3, be3 = sccl.sccl_cost_fit_intercept(a, b, a * alpha + b * beta)
+    assert abs(z0) < 1e-12 and al3 == pytest.approx(al2, rel=1e-6) and be3 == pytest.approx(be2, rel=1e-6)
+    with pytest.raises(sccl.ScclError):                    # a constant column a: t0 and alpha cannot be told apart
+        sccl.sccl_cost_fit_intercept([3.0, 3.0, 3.0, 3.0], [1.0, 2.0, 5.0, 9.0], [1.0, 2.0, 3.0, 4.0])
+    with pytest.raises(sccl.ScclError):
+        sccl.sccl_cost_fit_intercept([1.0, 2.0], [2.0, 5.0], [1.0, 2.0])
