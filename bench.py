@@ -309,6 +309,43 @@ def sweep(wl, steps, warmup):
     print(json.dumps({"best": best}), flush=True)
 
 
+def crossover(steps, warmup):
+    """Both lowerings of sccl_execute on twelve schedules at total sizes from 64 KiB to 256 MiB (all ranks together),
+    and which one SCCL_LOWER_AUTO picks: the evidence behind the automatic choice.  One JSON line per (schedule,
+    size); `auto_is_best` allows 3 % of noise."""
+    import dataclasses
+    from paper_2008_08708_amd import schedule_file, sccl, workloads
+    names = ["cfg1", "cfg2", "cfg3", "cfg4b", "alltoall", "broadcast", "reduce", "gather"]
+    wls = [workloads.WORKLOADS[k] for k in names]
+    wls += [workloads.sweep_workload(c, 1024, a) for c in ("allgather", "allreduce") for a in ("bandwidth", "latency")]
+    wrong = 0
+    for wl in wls:
+        sf = schedule_file.load(wl.schedule)
+        unit = sf.num_nodes * sf.positions_per_rank * 16                       # one 16-byte vector per chunk position
+        for total in [1 << e for e in range(16, 29, 2)]:
+            per_rank = max(1, total // unit) * sf.positions_per_rank * 16
+            w = dataclasses.replace(wl, bytes_per_rank=per_rank)
+            res = {}
+            for key, low in (("auto", 0), ("memory", 1), ("staged", 2)):
+                try:
+                    r = time_workload(w, steps, warmup, {"lowering": low} if low else None)
+                except sccl.ScclError:
+                    res[key] = None
+                    continue
+                m = sorted(r["ms"])
+                res[key] = round(m[len(m) // 2] * 1e3, 2)
+                if key == "auto":
+                    st = r["stats"]
+            best = min(v for k, v in res.items() if k != "auto" and v is not None)
+            ok = res["auto"] <= 1.03 * best + 0.3
+            wrong += not ok
+            print(json.dumps({"schedule": wl.schedule, "total_bytes": per_rank * sf.num_nodes, "auto": LOWERING_NAMES[st["lowering"]],
+                              "us_auto": res["auto"], "us_memory": res["memory"], "us_staged": res["staged"],
+                              "groups_per_chunk": st["max_chunk_groups"], "levels": st["num_levels"],
+                              "staged_levels": st["staged_levels"], "staged_items": st["num_slices"], "auto_is_best": ok}), flush=True)
+    print(json.dumps({"choices_that_lose_more_than_3_percent": wrong}), flush=True)
+
+
 def report(path, torch, workloads, sccl):
     """Times every configuration under every lowering, warm and cold, beside the oracle; the torus pair the
     cost model chooses between; and the streaming ceilings.  Markdown to `path`."""
@@ -446,6 +483,8 @@ def main():
     ap.add_argument("--no-ceilings", action="store_true", help="skip the plain streaming kernels")
     ap.add_argument("--ceilings", action="store_true", help="only measure the plain streaming kernels; one JSON line")
     ap.add_argument("--report", default="", metavar="FILE", help="also time the other configurations; markdown table to FILE")
+    ap.add_argument("--crossover", action="store_true",
+                    help="instead of the benchmark line: both lowerings on twelve schedules over a range of sizes, one JSON line each")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: time --workload under every launch shape of both kernels "
                          "(the paper's search over thread-block count and size, section 4) and print one JSON line each")
@@ -473,6 +512,9 @@ def main():
         wl = workloads.sweep_workload(parts[1], int(parts[2]), parts[3] if len(parts) > 3 else "bandwidth")
     else:
         wl = workloads.WORKLOADS[args.workload]
+    if args.crossover:
+        crossover(args.steps, args.warmup)
+        return
     if args.sweep:
         sweep(wl, args.steps, args.warmup)
         return

@@ -140,9 +140,9 @@ typedef struct {
  *                      than 256 dependency levels per chunk: SCCL_ERR_INVALID_ARG if asked for explicitly
  *                      and that does not hold.
  *   SCCL_LOWER_AUTO    from measured crossovers: staged when possible and either the P rank buffers together
- *                      are at most 512 KiB (launch overhead dominates; staged never loses), or the schedule
- *                      has long chains that levels shorten (some chunk has at least 8 groups and at least
- *                      twice as many groups as levels) and the staged kernel has at most 4096 work items;
+ *                      are at most 512 KiB (launch overhead dominates; staged never loses), or staging saves at
+ *                      least three memory round trips per chunk (groups of the longest chunk chain minus
+ *                      sccl_stats_t.staged_levels) and the staged kernel has at most 4096 work items;
  *                      through memory otherwise. */
 #define SCCL_LOWER_AUTO   0
 #define SCCL_LOWER_MEMORY 1
@@ -187,6 +187,10 @@ typedef struct {
     int32_t num_cells_loaded;      /* of those, read before any send writes them */
     int32_t num_cells_stored;      /* of those, written by some send */
     int32_t num_levels;            /* length of the longest chain of dependent groups (of any one chunk) */
+    int32_t staged_levels;         /* levels the staged kernel runs: copies whose source stays put are propagated at
+                                      plan time (the destination is stored from the source's place in the local
+                                      data share), so an Allgather has 0 and an Allreduce about half of num_levels */
+    int32_t staged_tasks;          /* cell writes left after that, over all chunks */
     int32_t max_level_tasks;       /* most cell writes any one level of any one chunk performs */
     int32_t max_chunk_groups;      /* most groups any one chunk has (its chain in the through-memory kernel) */
     int32_t slice_vectors, staged_threads;

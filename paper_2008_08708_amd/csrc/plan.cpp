@@ -30,6 +30,14 @@ int elem_bytes(sccl_dtype_t d) { return d == SCCL_F16 ? 2 : 4; }
 
 // Tables of the staged lowering: one block per chunk, from the chunk's op list in step order (plan.prog).
 // Returns false when some chunk has more levels than the kernel keeps in registers.
+//
+// Copies are propagated at plan time.  Inside the local data share a COPY moves bits from one cell to another and
+// nothing else, so when the source's storage is never written again (and neither is the destination) the
+// destination simply ALIASES the source's storage: no task is emitted, later reads of the destination read the
+// source's storage, and the final store of the destination is made from there.  What is stored where is unchanged
+// bit for bit.  An Allgather, a Broadcast, a Scatter, a Gather or an Alltoall then has no level at all (load the
+// holder's slice once, store it to every cell post or a forwarding step names), and an Allreduce keeps only the
+// levels of its reducing half.  A copy that does not meet the condition stays a task.
 bool build_staged_tables(const sccl_plan& plan, sccl_staged* out) {
     sccl_staged& sg = *out;
     sg = sccl_staged();
@@ -44,7 +52,8 @@ bool build_staged_tables(const sccl_plan& plan, sccl_staged* out) {
             w += 2 + (plan.prog[(size_t)w] >> 8);
         }
         const size_t n_groups = groups.size();
-        // pass 1: the cells, and which of them are read before they are written
+        // pass 1: the cells (rank, chunk position) the chunk's sends touch, which of them are read before they are
+        // written, and the last group that writes each
         std::map<int32_t, int32_t> first_access;          // operand word -> 0 read first, 1 written first
         std::vector<int32_t> order;                       // operand words by first appearance
         auto touch = [&](int32_t w, int32_t how) {
@@ -56,72 +65,124 @@ bool build_staged_tables(const sccl_plan& plan, sccl_staged* out) {
             touch(op[1], 0);                              // copy: the source; reduce: the destination's own value
             for (int32_t j = 0; j < k; j++) touch(op[2 + j], reduce ? 0 : 1);
         }
-        std::map<int32_t, int32_t> cell;                  // operand word -> cell id, loaded cells first
+        std::map<int32_t, int32_t> cell;                  // operand word -> logical cell id, read-first cells first
         std::vector<int32_t> cell_word;
-        int32_t n_in = 0;
+        int32_t n_read_first = 0;
         for (int pass = 0; pass < 2; pass++)
             for (int32_t w : order)
-                if (first_access[w] == pass) { cell[w] = (int32_t)cell_word.size(); cell_word.push_back(w); n_in += pass == 0; }
+                if (first_access[w] == pass) { cell[w] = (int32_t)cell_word.size(); cell_word.push_back(w); n_read_first += pass == 0; }
         const int32_t n_cells = (int32_t)cell_word.size();
-
-        // pass 2: levels.  wl/rl: level of the last write of a cell / highest level that read it.
-        std::vector<int32_t> wl((size_t)n_cells, 0), rl((size_t)n_cells, 0), level(n_groups, 0);
+        std::vector<int32_t> last_write((size_t)n_cells, -1);
         std::vector<uint8_t> written((size_t)n_cells, 0);
-        int32_t n_levels = 0;
         for (size_t g = 0; g < n_groups; g++) {
             const int32_t* op = groups[g];
             const int32_t k = op[0] >> 8;
-            const bool reduce = (op[0] & OP_KIND_REDUCE) != 0;
-            const int32_t anchor = cell[op[1]];
-            int32_t lv = 1;
-            if (reduce) {
-                // reads the destination and the sources, writes the destination (its own read is no conflict)
-                lv = std::max(lv, std::max(wl[(size_t)anchor], rl[(size_t)anchor]) + 1);
-                for (int32_t j = 0; j < k; j++) lv = std::max(lv, wl[(size_t)cell[op[2 + j]]] + 1);
+            if (op[0] & OP_KIND_REDUCE) { last_write[(size_t)cell[op[1]]] = (int32_t)g; written[(size_t)cell[op[1]]] = 1; }
+            else for (int32_t j = 0; j < k; j++) { last_write[(size_t)cell[op[2 + j]]] = (int32_t)g; written[(size_t)cell[op[2 + j]]] = 1; }
+        }
+
+        // pass 2: dependency levels of the schedule itself (statistics; the through-memory kernel's chain).
+        // wl/rl: level of the last write of a cell / highest level that read it.
+        int32_t sched_levels = 0;
+        {
+            std::vector<int32_t> wl((size_t)n_cells, 0), rl((size_t)n_cells, 0);
+            for (size_t g = 0; g < n_groups; g++) {
+                const int32_t* op = groups[g];
+                const int32_t k = op[0] >> 8;
+                const bool reduce = (op[0] & OP_KIND_REDUCE) != 0;
+                const int32_t anchor = cell[op[1]];
+                int32_t lv = 1;
+                if (reduce) {
+                    lv = std::max(lv, std::max(wl[(size_t)anchor], rl[(size_t)anchor]) + 1);
+                    for (int32_t j = 0; j < k; j++) lv = std::max(lv, wl[(size_t)cell[op[2 + j]]] + 1);
+                    for (int32_t j = 0; j < k; j++) { int32_t& r = rl[(size_t)cell[op[2 + j]]]; r = std::max(r, lv); }
+                    wl[(size_t)anchor] = lv;
+                } else {
+                    lv = std::max(lv, wl[(size_t)anchor] + 1);
+                    for (int32_t j = 0; j < k; j++) {
+                        const int32_t d = cell[op[2 + j]];
+                        lv = std::max(lv, std::max(wl[(size_t)d], rl[(size_t)d]) + 1);
+                    }
+                    rl[(size_t)anchor] = std::max(rl[(size_t)anchor], lv);
+                    for (int32_t j = 0; j < k; j++) wl[(size_t)cell[op[2 + j]]] = lv;
+                }
+                sched_levels = std::max(sched_levels, lv);
+            }
+        }
+
+        // pass 3: copy propagation.  alias[x] = the logical cell whose STORAGE holds x's current value.  A real
+        // task reads storages and writes its destination's own storage.
+        struct Task { int32_t dst; std::vector<int32_t> srcs; bool reduce; int32_t level = 0; };
+        std::vector<Task> tasks_in_order;
+        std::vector<int32_t> alias((size_t)n_cells);
+        std::vector<uint8_t> has_storage((size_t)n_cells, 0);
+        for (int32_t i = 0; i < n_cells; i++) { alias[(size_t)i] = i; has_storage[(size_t)i] = i < n_read_first; }
+        for (size_t g = 0; g < n_groups; g++) {
+            const int32_t* op = groups[g];
+            const int32_t k = op[0] >> 8;
+            if (op[0] & OP_KIND_REDUCE) {
+                const int32_t d = cell[op[1]];             // alias[d] == d here: a copy into a cell that is written again is never elided
+                Task t{d, {}, true};
+                for (int32_t j = 0; j < k; j++) t.srcs.push_back(alias[(size_t)cell[op[2 + j]]]);
+                tasks_in_order.push_back(std::move(t));
+                alias[(size_t)d] = d; has_storage[(size_t)d] = 1;
             } else {
-                lv = std::max(lv, wl[(size_t)anchor] + 1);
+                const int32_t r = alias[(size_t)cell[op[1]]];
                 for (int32_t j = 0; j < k; j++) {
                     const int32_t d = cell[op[2 + j]];
-                    lv = std::max(lv, std::max(wl[(size_t)d], rl[(size_t)d]) + 1);
+                    if (last_write[(size_t)r] <= (int32_t)g && last_write[(size_t)d] <= (int32_t)g) {
+                        alias[(size_t)d] = r;              // elided: d's value lives in r's storage to the end
+                    } else {
+                        tasks_in_order.push_back(Task{d, {r}, false});
+                        alias[(size_t)d] = d; has_storage[(size_t)d] = 1;
+                    }
                 }
             }
-            level[g] = lv;
-            n_levels = std::max(n_levels, lv);
-            if (reduce) {
-                for (int32_t j = 0; j < k; j++) { int32_t& r = rl[(size_t)cell[op[2 + j]]]; r = std::max(r, lv); }
-                wl[(size_t)anchor] = lv; written[(size_t)anchor] = 1;
-            } else {
-                rl[(size_t)anchor] = std::max(rl[(size_t)anchor], lv);
-                for (int32_t j = 0; j < k; j++) { const int32_t d = cell[op[2 + j]]; wl[(size_t)d] = lv; written[(size_t)d] = 1; }
+        }
+        // storages: the cells to load first (read before written), then the cells real tasks write first
+        std::vector<int32_t> storage((size_t)n_cells, -1), storage_word;
+        for (int32_t i = 0; i < n_cells; i++)
+            if (has_storage[(size_t)i]) { storage[(size_t)i] = (int32_t)storage_word.size(); storage_word.push_back(cell_word[(size_t)i]); }
+        const int32_t n_storage = (int32_t)storage_word.size(), n_in = n_read_first;
+
+        // pass 4: levels of the real tasks, by storage
+        int32_t n_levels = 0;
+        {
+            std::vector<int32_t> wl((size_t)n_storage, 0), rl((size_t)n_storage, 0);
+            for (Task& t : tasks_in_order) {
+                const int32_t d = storage[(size_t)t.dst];
+                int32_t lv = std::max(wl[(size_t)d], rl[(size_t)d]) + 1;      // its own read of the destination is no conflict
+                for (int32_t sc : t.srcs) lv = std::max(lv, wl[(size_t)storage[(size_t)sc]] + 1);
+                for (int32_t sc : t.srcs) { int32_t& r = rl[(size_t)storage[(size_t)sc]]; r = std::max(r, lv); }
+                wl[(size_t)d] = lv;
+                t.level = lv;
+                n_levels = std::max(n_levels, lv);
             }
         }
         if (n_levels >= STAGED_MAX_LEVELS) return false;
 
-        // pass 3: the tasks, level by level, groups in step order inside a level.  A task record is eight
-        // words: destination cell | k << 16, then for a copy (k == 0) the source cell, for a reduce the index
-        // of its fifth source in the overflow list, then the first four sources, then padding.
+        // pass 5: the records, level by level, tasks in step order inside a level.  A task record is eight
+        // words: destination | k << 16, then for a copy (k == 0) the source, for a reduce the index of its fifth
+        // source in the overflow list, then the first four sources, then padding.  All are storage ids.
         std::vector<int32_t> out_cells, lev_first((size_t)n_levels + 1, 0), tasks, extra;
         for (int32_t i = 0; i < n_cells; i++)
-            if (written[(size_t)i]) { out_cells.push_back(i); out_cells.push_back(cell_word[(size_t)i]); }
+            if (written[(size_t)i]) { out_cells.push_back(storage[(size_t)alias[(size_t)i]]); out_cells.push_back(cell_word[(size_t)i]); }
         int32_t widest = 0;
         for (int32_t lv = 1; lv <= n_levels; lv++) {
             lev_first[(size_t)lv - 1] = (int32_t)(tasks.size() / STAGED_TASK_WORDS);
-            for (size_t g = 0; g < n_groups; g++) {
-                if (level[g] != lv) continue;
-                const int32_t* op = groups[g];
-                const int32_t k = op[0] >> 8;
-                if (op[0] & OP_KIND_REDUCE) {
-                    int32_t rec[STAGED_TASK_WORDS] = {cell[op[1]] | (k << 16), (int32_t)extra.size(), 0, 0, 0, 0, 0, 0};
+            for (const Task& t : tasks_in_order) {
+                if (t.level != lv) continue;
+                const int32_t k = (int32_t)t.srcs.size();
+                if (t.reduce) {
+                    int32_t rec[STAGED_TASK_WORDS] = {storage[(size_t)t.dst] | (k << 16), (int32_t)extra.size(), 0, 0, 0, 0, 0, 0};
                     for (int32_t j = 0; j < k; j++) {
-                        if (j < 4) rec[2 + j] = cell[op[2 + j]];
-                        else extra.push_back(cell[op[2 + j]]);
+                        if (j < 4) rec[2 + j] = storage[(size_t)t.srcs[(size_t)j]];
+                        else extra.push_back(storage[(size_t)t.srcs[(size_t)j]]);
                     }
                     tasks.insert(tasks.end(), rec, rec + STAGED_TASK_WORDS);
                 } else {
-                    for (int32_t j = 0; j < k; j++) {
-                        const int32_t rec[STAGED_TASK_WORDS] = {cell[op[2 + j]], cell[op[1]], 0, 0, 0, 0, 0, 0};
-                        tasks.insert(tasks.end(), rec, rec + STAGED_TASK_WORDS);
-                    }
+                    const int32_t rec[STAGED_TASK_WORDS] = {storage[(size_t)t.dst], storage[(size_t)t.srcs[0]], 0, 0, 0, 0, 0, 0};
+                    tasks.insert(tasks.end(), rec, rec + STAGED_TASK_WORDS);
                 }
             }
             widest = std::max(widest, (int32_t)(tasks.size() / STAGED_TASK_WORDS) - lev_first[(size_t)lv - 1]);
@@ -131,14 +192,15 @@ bool build_staged_tables(const sccl_plan& plan, sccl_staged* out) {
 
         const int32_t n_out = (int32_t)(out_cells.size() / 2), n_tasks = (int32_t)(tasks.size() / STAGED_TASK_WORDS);
         Pieces& pc = pieces[(size_t)c];
-        pc.cell_word = cell_word; pc.out_cells = out_cells; pc.lev_first = lev_first; pc.tasks = tasks; pc.extra = extra;
+        pc.cell_word = storage_word; pc.out_cells = out_cells; pc.lev_first = lev_first; pc.tasks = tasks; pc.extra = extra;
         pc.n_in = n_in; pc.n_levels = n_levels;
 
         sg.n_cells += n_cells; sg.n_in += n_in; sg.n_out += n_out; sg.n_tasks += n_tasks;
-        sg.n_levels = std::max(sg.n_levels, n_levels);
+        sg.n_levels = std::max(sg.n_levels, sched_levels);
+        sg.staged_levels = std::max(sg.staged_levels, n_levels);
         sg.max_level_tasks = std::max(sg.max_level_tasks, widest);
         sg.max_chunk_groups = std::max(sg.max_chunk_groups, (int32_t)n_groups);
-        sg.max_chunk_cells = std::max(sg.max_chunk_cells, n_cells);
+        sg.max_chunk_cells = std::max(sg.max_chunk_cells, n_storage);
         sg.max_chunk_in = std::max(sg.max_chunk_in, n_in);
         sg.max_chunk_out = std::max(sg.max_chunk_out, n_out);
     }
@@ -482,7 +544,7 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
     // ---- the staged lowering: tables, then the slice a workgroup stages at a time
     sccl_staged& sg = plan->staged;
     const int32_t want_lowering = opts ? opts->lowering : SCCL_LOWER_AUTO;
-    if (build_staged_tables(*plan, &sg) && sg.n_tasks > 0 && plan->vecs_per_chunk > 0) {
+    if (build_staged_tables(*plan, &sg) && sg.n_out > 0 && plan->vecs_per_chunk > 0) {
         const int64_t block_bytes = (int64_t)sg.max_block_words * 4;
         const int64_t room = STAGED_LDS_LIMIT - block_bytes;                  // bytes left for the cells
         const int64_t max_slice = room > 0 ? room / ((int64_t)sg.max_chunk_cells * W) : 0;   // vectors per cell that fit
@@ -510,20 +572,22 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
         }
     }
     if (want_lowering == SCCL_LOWER_STAGED && !sg.available) return SCCL_ERR_INVALID_ARG;
-    // SCCL_LOWER_AUTO, from the measured crossovers: the staged kernel never loses while launch overhead dominates
-    // (tiny totals); beyond that it wins where a chunk's chain of groups is long AND shortens when groups of one
-    // level run together (at least 8 groups and twice as many groups as levels: tree-shaped schedules on multi-hop
-    // topologies, not rings and not two-step schedules), and only while its single-wavefront work items stay few.
+    // SCCL_LOWER_AUTO, from the measured crossovers (both lowerings on twelve schedules, 64 KiB to 256 MiB in all): the
+    // staged kernel never loses while launch overhead dominates (tiny totals); beyond that it wins where it saves
+    // memory round trips -- the through-memory kernel pays one per group of a chunk's chain, the staged kernel one
+    // per level that is left after copy propagation, so the saving is their difference (12 on the torus Allgather,
+    // 18 on its Allreduce, 5 on a Broadcast tree, 7 on a ring Allreduce; 2 on two-hop schedules such as Gather or
+    // Alltoall, which do not pay for it) -- and only while its single-wavefront work items stay few.
     const bool tiny = (int64_t)P * st.bytes_per_rank <= STAGED_AUTO_TINY_BYTES;
-    const bool long_chains = sg.max_chunk_groups >= 8 && sg.max_chunk_groups >= 2 * sg.n_levels;
+    const bool saves_round_trips = sg.max_chunk_groups - sg.staged_levels >= STAGED_AUTO_MIN_SAVING;
     const bool few_items = sg.num_slices <= STAGED_AUTO_MAX_ITEMS;
-    const bool automatic = sg.available && (tiny || (long_chains && few_items));
+    const bool automatic = sg.available && (tiny || (saves_round_trips && few_items));
     plan->lowering = (want_lowering == SCCL_LOWER_STAGED || (want_lowering == SCCL_LOWER_AUTO && automatic))
                          ? SCCL_LOWER_STAGED : SCCL_LOWER_MEMORY;
     st.lowering = plan->lowering;
     st.staged_available = sg.available ? 1 : 0;
     st.num_cells = sg.n_cells; st.num_cells_loaded = sg.n_in; st.num_cells_stored = sg.n_out;
-    st.num_levels = sg.n_levels; st.max_level_tasks = sg.max_level_tasks; st.max_chunk_groups = sg.max_chunk_groups;
+    st.num_levels = sg.n_levels; st.staged_levels = sg.staged_levels; st.staged_tasks = sg.n_tasks; st.max_level_tasks = sg.max_level_tasks; st.max_chunk_groups = sg.max_chunk_groups;
     st.slice_vectors = sg.available ? (1 << sg.log_slice_vectors) : 0;
     st.staged_threads = sg.threads;
     st.staged_lds_bytes = sg.lds_bytes;

@@ -21,20 +21,24 @@ constexpr int32_t OPERAND_RANK_MASK = (1 << OPERAND_RANK_BITS) - 1;
 constexpr int32_t MAX_SLOTS = 1 << (31 - OPERAND_RANK_BITS);
 
 // Tables of the staged lowering, one block per chunk (chunks never share memory, so each has its own cells,
-// levels and tasks).  A *cell* is one (rank, chunk position) pair some send of the chunk touches; the cells a send
-// reads before any send writes them come first (they are what a workgroup loads).  A *task* is one cell write:
-// a copy group with k destinations is k tasks, a reduce group is one.  Tasks are sorted by dependency level: a
-// group's level is one more than the highest level among the earlier groups whose cells it reads after they
-// wrote them, or writes after they read or wrote them, so the tasks of one level touch no cell in conflicting
-// ways and a workgroup barrier between levels is all the ordering needed.
+// levels and tasks).  A *cell* is one (rank, chunk position) pair some send of the chunk touches.  Cells that need
+// room in the local data share ("storages") are numbered: those a send reads before any send writes them come
+// first (they are what a workgroup loads), then those a task writes first; a cell that only ever receives a
+// copy of a value that stays put has no storage of its own and is stored from the storage that holds its value
+// (copy propagation, plan.cpp).  A *task* is one cell write that is left after that: a reduce group, or one
+// destination of a copy group.  Tasks are sorted by dependency level: a task's level is one more than the highest
+// level among the earlier tasks whose storages it reads after they wrote them, or writes after they read or wrote
+// them, so the tasks of one level touch no storage in conflicting ways and a workgroup barrier between levels is
+// all the ordering needed.
 //   table:  G blocks of one stride (the largest block), so that a workgroup can fetch what it needs first
 //           (header, cell words, level table) before it knows the header.
-//   block:  8 header words        cells | loaded cells | stored cells | levels | tasks | overflow sources | 0 | 0
-//           cell words            operand word (rank | position << 8) of every cell; room for the most cells any
+//   block:  8 header words        storages | loaded storages | stored cells | levels | tasks | overflow sources | 0 | 0
+//           cell words            operand word (rank | position << 8) of every storage; room for the most any
 //                                 chunk has, rounded up to 4
 //           levels + 2            first task of every level, the end, the end again
-//           2 x stored cells      the cells to store at the end: id, operand word; then padding to 4 words
-//           8 x tasks             per task: destination cell | k << 16 ; k == 0: the source cell of a copy,
+//           2 x stored cells      the cells to store at the end: the storage that holds the value, the cell's
+//                                 operand word; then padding to 4 words
+//           8 x tasks             per task: destination storage | k << 16 ; k == 0: the source storage of a copy,
 //                                 else the index of the task's fifth source in the overflow list ; the
 //                                 first four source cells in schedule order ; two words of padding
 //           overflow sources      fifth and later sources of reduce tasks with more than four; padding
@@ -43,12 +47,14 @@ constexpr int32_t STAGED_TASK_WORDS = 8;
 constexpr int32_t STAGED_MAX_LEVELS = 256;                // a wavefront keeps the level table in four registers per lane
 constexpr int64_t STAGED_LDS_LIMIT = 160 * 1024;          // local data share of one gfx950 compute unit
 constexpr int64_t STAGED_AUTO_TINY_BYTES = 512ll << 10;   // all rank buffers together: launch overhead dominates
-constexpr int64_t STAGED_AUTO_MAX_ITEMS = 4096;           // work items (16 per compute unit) up to which long chains pay
+constexpr int32_t STAGED_AUTO_MIN_SAVING = 3;             // memory round trips per chunk the staged kernel must save to be chosen
+constexpr int64_t STAGED_AUTO_MAX_ITEMS = 4096;           // work items (16 per compute unit) up to which the saving pays
 
 struct sccl_staged {
     bool available = false;
     // totals over the chunks (statistics) and maxima over the chunks (sizes a workgroup needs)
-    int32_t n_cells = 0, n_in = 0, n_out = 0, n_levels = 0, n_tasks = 0, max_level_tasks = 0;
+    // n_levels: dependency levels of the schedule; staged_levels: levels left after copy propagation (what the kernel runs)
+    int32_t n_cells = 0, n_in = 0, n_out = 0, n_levels = 0, staged_levels = 0, n_tasks = 0, max_level_tasks = 0;
     int32_t max_chunk_groups = 0;
     int32_t max_chunk_cells = 0, max_chunk_in = 0, max_chunk_out = 0, max_block_words = 0, cell_words_room = 0;
     std::vector<int32_t> table;

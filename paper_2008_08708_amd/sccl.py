@@ -76,7 +76,8 @@ class sccl_stats_t(ctypes.Structure):
                 ("num_work_items", ctypes.c_int64), ("grid_workgroups", ctypes.c_int32),
                 ("lowering", ctypes.c_int32), ("staged_available", ctypes.c_int32), ("num_cells", ctypes.c_int32),
                 ("num_cells_loaded", ctypes.c_int32), ("num_cells_stored", ctypes.c_int32),
-                ("num_levels", ctypes.c_int32), ("max_level_tasks", ctypes.c_int32), ("max_chunk_groups", ctypes.c_int32),
+                ("num_levels", ctypes.c_int32), ("staged_levels", ctypes.c_int32), ("staged_tasks", ctypes.c_int32),
+                ("max_level_tasks", ctypes.c_int32), ("max_chunk_groups", ctypes.c_int32),
                 ("slice_vectors", ctypes.c_int32), ("staged_threads", ctypes.c_int32),
                 ("staged_lds_bytes", ctypes.c_int32), ("num_slices", ctypes.c_int64),
                 ("static_table_bytes", ctypes.c_int64)]

@@ -105,3 +105,15 @@ def test_repeated_execution_reuses_the_plan():
         torch.cuda.synchronize()
         assert_same_bits(want, [d.cpu().numpy() for d in dev])
     sccl.sccl_plan_destroy(plan)
+
+
+def test_copies_that_cannot_be_propagated_stay_tasks():
+    # the staged lowering stores the destination of a COPY from the source's place in the local data share unless
+    # source or destination is written again: these schedules do exactly that (and leave a partial sum behind)
+    from test_host_plan import awkward_copy_schedules
+    for i, (topo, coll, sched) in enumerate(awkward_copy_schedules()):
+        for dtype, dist in (("f32", "uniform"), ("f16", "normal"), ("i32", "u32")):
+            epc = 4 * 37 + 4
+            bufs = host_inputs(dist, dtype, 107 + i, 3, 1, epc)
+            want, got = run_both(topo, coll, sched, dtype, bufs, epc, label=f"awkward-copy-{i}-{dtype}")
+            assert_same_bits(want, got)

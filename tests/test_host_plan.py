@@ -310,12 +310,17 @@ def test_staged_lowering_choice_and_limits():
     for epc, want in ((1 << 12, sccl.SCCL_LOWER_STAGED), (1 << 13, sccl.SCCL_LOWER_MEMORY)):
         _, st = plan_status(topo, arc, ar, "f32", epc)
         assert P_bytes(st) == 16 * 64 * epc * 4 and st["lowering"] == want
-    # rings and two-step schedules have no chain that levels shorten: staged only while tiny (512 KiB over all ranks)
+    # a ring Allreduce saves 7 of its 14 round trips per chunk: staged while the work items are few (4096), by size beyond
     ring, rag = tp.ring(8), col.allgather(8, 4)
     rar, rarc = gen.compose_allreduce(gen.ring_allgather(8, 4), rag)
-    for epc, want in ((512, sccl.SCCL_LOWER_STAGED), (1024, sccl.SCCL_LOWER_MEMORY)):      # 32 chunks x 8 ranks x epc x 4 B
-        _, st = plan_status(ring, rarc, rar, "f32", epc)
-        assert st["lowering"] == want and st["max_chunk_groups"] == st["num_levels"] == 14
+    for epc, want in ((512, sccl.SCCL_LOWER_STAGED), (8192, sccl.SCCL_LOWER_STAGED), (16384, sccl.SCCL_LOWER_MEMORY)):
+        _, st = plan_status(ring, rarc, rar, "f32", epc)                                    # 32 chunks x epc / 4 / 16 work items
+        assert st["lowering"] == want and st["max_chunk_groups"] == st["num_levels"] == 14 and st["staged_levels"] == 7
+    # two-hop schedules save too little: staged only while tiny (512 KiB over all ranks)
+    g8, gc = tp.dgx1(), col.gather(8, 1, 0)
+    gs = gen.greedy_route(g8, gc)
+    for epc, want in ((2048, sccl.SCCL_LOWER_STAGED), (4096, sccl.SCCL_LOWER_MEMORY)):      # 8 chunks x 8 ranks x epc x 4 B
+        assert plan_status(g8, gc, gs, "f32", epc)[1]["lowering"] == want
     k8, kag = tp.complete(8), col.allgather(8, 1)
     kar, karc = gen.compose_allreduce(gen.greedy_bfs(k8, kag), kag)
     assert plan_status(k8, karc, kar, "f32", 1 << 16)[1]["lowering"] == sccl.SCCL_LOWER_MEMORY       # 2 groups per chunk
@@ -382,3 +387,40 @@ def test_static_table_size_is_reported_and_oversized_plans_are_refused_without_a
     with pytest.raises(ValueError):
         sccl.sccl_execute_static(p, fake[:3], stream=0)
     sccl.sccl_plan_destroy(p)
+
+
+def awkward_copy_schedules():
+    """Valid combining schedules on three fully connected ranks in which a COPY cannot be propagated by the staged
+    lowering: its source (first) or its destination (second) is written again afterwards."""
+    from oracle.collective import Collective
+    topo = tp.complete(3)
+    pre = np.ones((1, 3), dtype=np.uint8)
+    for last, root in (((0, 2, 0, 2, REDUCE), 0), ((0, 2, 1, 2, REDUCE), 1)):
+        post = np.zeros((1, 3), dtype=np.uint8)
+        post[0, root] = 1
+        coll = Collective("reduce-with-a-detour", 3, 1, pre, post, True)
+        sched = make_schedule([1, 1, 1], [(0, 1, 0, 0, REDUCE), (0, 0, 1, 1, COPY), last])
+        yield topo, coll, sched
+
+
+def test_copy_propagation_of_the_staged_lowering():
+    # non-combining collectives: every copy's source stays put, so no level and no task is left
+    for topo, coll in ((tp.torus2d(4, 4), col.allgather(16, 4)), (tp.dgx1(), col.alltoall(8, 8)), (tp.hcm8(), col.broadcast(8, 3, 1))):
+        s = gen.greedy_route(topo, coll) if coll.name != "allgather" else gen.greedy_bfs(topo, coll)
+        _, st = plan_status(topo, coll, s, "f32", 64)
+        assert st["num_levels"] >= 2 and st["staged_levels"] == 0 and st["staged_tasks"] == 0
+    # Allreduce = Reducescatter ; Allgather: the reducing half keeps its levels, the copying half has none
+    for topo, C, kind in ((tp.torus2d(4, 4), 4, "greedy"), (tp.ring(8), 2, "ring"), (tp.hcm8(), 1, "greedy")):
+        ag = col.allgather(topo.num_nodes, C)
+        base = gen.ring_allgather(8, C) if kind == "ring" else gen.greedy_bfs(topo, ag)
+        ar, arc = gen.compose_allreduce(base, ag)
+        rs, rsc = gen.reducescatter_from(base, ag)
+        _, st = plan_status(topo, arc, ar, "f32", 64)
+        _, st_rs = plan_status(topo.reversed(), rsc, rs, "f32", 64)
+        assert st["staged_levels"] == st_rs["staged_levels"] == st_rs["num_levels"] == st["num_levels"] // 2
+        assert st["staged_tasks"] == st_rs["staged_tasks"] == st["num_reduce_groups"]
+    # copies whose source or destination is written again stay tasks
+    for topo, coll, sched in awkward_copy_schedules():
+        assert validate(topo, coll, sched).ok
+        _, st = plan_status(topo, coll, sched, "f32", 64)
+        assert st["staged_tasks"] == 3 and st["staged_levels"] == st["num_levels"] == 3
