@@ -332,7 +332,7 @@ struct StagedArgs {
     int32_t log_slice;            // vectors per slice = 1 << log_slice
     int32_t block_words;          // stride of the chunk blocks, in words (a multiple of 4)
     int32_t cell_words_room;      // words reserved for cell words in every block
-    int32_t pad;
+    uint32_t identity_off;        // byte offset of the identity storage in a workgroup's cell area
     char* bufs[SCCL_MAX_RANKS];
 };
 
@@ -345,45 +345,55 @@ __device__ __forceinline__ char* rank_base(uint32_t lo, uint32_t hi, int32_t ran
 // Offsets of the parts of one chunk's block inside the local copy, and their sizes.
 struct StagedBlock { int32_t n_in, n_out, n_levels, off_out, off_lev, off_task, off_extra; };
 
-// One task record as a lane holds it (t0 < 0: no task).
-struct StagedTask { int32_t t0, t1, s[4]; };
+// One task record as a lane holds it: destination byte offset | fan-in << 24, overflow index, four source byte offsets.
+struct StagedTask { int32_t w0, w1, s[4]; };
 
-__device__ __forceinline__ void fetch_task(StagedTask& t, const int32_t* tab, const StagedBlock& b,
+// The record of the task lane slot i runs in the level [t_lo, t_hi): task t_lo + (i >> ls), vector i & (slice - 1).
+// Slots beyond the level fetch the level's last record instead (valid memory, same code path) and return false.
+__device__ __forceinline__ bool fetch_task(StagedTask& t, const int32_t* tab, const StagedBlock& b,
                                            int32_t t_lo, int32_t t_hi, int32_t i, int32_t ls) {
     const int32_t task = t_lo + (i >> ls);
-    t.t0 = -1;
-    if (task < t_hi) {
-        const u32x4* rec = (const u32x4*)(tab + b.off_task + STAGED_TASK_WORDS * task);   // 16-byte aligned
-        const u32x4 lo = rec[0];
-        const u32x2 hi = *(const u32x2*)(rec + 1);
-        t.t0 = (int32_t)lo.x; t.t1 = (int32_t)lo.y; t.s[0] = (int32_t)lo.z; t.s[1] = (int32_t)lo.w;
-        t.s[2] = (int32_t)hi.x; t.s[3] = (int32_t)hi.y;
-    }
+    const int32_t last = t_hi > 0 ? t_hi - 1 : 0;
+    const int32_t rd = task < t_hi ? task : last;
+    const u32x4* rec = (const u32x4*)(tab + b.off_task + STAGED_TASK_WORDS * rd);     // 16-byte aligned
+    const u32x4 lo = rec[0];
+    const u32x2 hi = *(const u32x2*)(rec + 1);
+    t.w0 = (int32_t)lo.x; t.w1 = (int32_t)lo.y; t.s[0] = (int32_t)lo.z; t.s[1] = (int32_t)lo.w;
+    t.s[2] = (int32_t)hi.x; t.s[3] = (int32_t)hi.y;
+    return task < t_hi;
 }
 
+// What the identity storage holds: adding it changes no bit of any sum (-0.0 for the floating types: x + (-0.0) is x
+// for every x, signed zeros and denormals included, in binary32, where binary16 operands are summed too; 0 for int32).
 template <int DT, int W>
-__device__ __forceinline__ void run_task(typename VecOf<W>::type* cells, const int32_t* tab, const StagedBlock& b,
-                                         const StagedTask& t, int32_t v, int32_t ls) {
+__device__ __forceinline__ typename VecOf<W>::type identity_vector() {
     typedef typename VecOf<W>::type V;
-    if (t.t0 < 0) return;
-    const int32_t dst = t.t0 & 0xffff, k = t.t0 >> 16;
-    if (k == 0) {
-        cells[(dst << ls) + v] = cells[(t.t1 << ls) + v];
-        return;
-    }
-    // the destination's own value first, then the sources in schedule order
+    uint32_t word = DT == SCCL_F32 ? 0x80000000u : DT == SCCL_F16 ? 0x80008000u : 0u;
+    uint32_t w4[4] = {word, word, word, word};
+    V v; __builtin_memcpy(&v, w4, W); return v;
+}
+
+// One task on one vector, the same instructions whatever the fan-in: the destination's own value first, then four
+// sources in schedule order (unused slots name the identity storage), then any further sources; a copy (fan-in 0)
+// takes the bits of its source instead of the sum.  `voff` is the byte offset of the lane's vector in a slice.
+template <int DT, int W>
+__device__ __forceinline__ void run_task(char* cells, const int32_t* tab, const StagedBlock& b,
+                                         const StagedTask& t, bool active, uint32_t voff) {
+    typedef typename VecOf<W>::type V;
+    const int32_t k = t.w0 >> STAGED_TASK_K_SHIFT;
+    const uint32_t dst = (uint32_t)(t.w0 & ((1 << STAGED_TASK_K_SHIFT) - 1)) + voff;
+    const V d = *(const V*)(cells + dst);
     V x[4];
-    const V d = cells[(dst << ls) + v];
 #pragma unroll
-    for (int j = 0; j < 4; j++)
-        if (j < k) x[j] = cells[(t.s[j] << ls) + v];
+    for (int j = 0; j < 4; j++) x[j] = *(const V*)(cells + (uint32_t)t.s[j] + voff);
     Acc<DT, W> acc;
     acc.init(d);
 #pragma unroll
-    for (int j = 0; j < 4; j++)
-        if (j < k) acc.add(x[j]);
-    for (int32_t j = 4; j < k; j++) acc.add(cells[(tab[b.off_extra + t.t1 + j - 4] << ls) + v]);
-    cells[(dst << ls) + v] = acc.template done<V>();
+    for (int j = 0; j < 4; j++) acc.add(x[j]);
+    for (int32_t j = 4; j < k; j++) acc.add(*(const V*)(cells + (uint32_t)tab[b.off_extra + t.w1 + j - 4] + voff));
+    V out = acc.template done<V>();
+    if (k == 0) out = x[0];
+    if (active) *(V*)(cells + dst) = out;
 }
 
 // First task of level l (any l >= 0; beyond the last level: the end) out of the wavefront's copy of the
@@ -408,6 +418,7 @@ __global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char staged_lds[];
     const int32_t* tab = (const int32_t*)staged_lds;               // the chunk's block
     V* cells = (V*)(staged_lds + (size_t)a.block_words * 4);
+    char* cell_bytes = (char*)cells;
     const int32_t tid = (int32_t)threadIdx.x, BT = (int32_t)blockDim.x;
     const bool one_wave = BT <= 64;
     const int32_t ls = a.log_slice, sv = 1 << ls, vmask = sv - 1;
@@ -455,6 +466,8 @@ __global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
             u32x4* dst = (u32x4*)staged_lds;
             for (int32_t i = tid; i < a.block_words / 4; i += BT) dst[i] = src[i];
         }
+        if (b.n_levels > 0)                                        // the identity storage, one slice long
+            for (int32_t i = tid; i < sv; i += BT) *(V*)(cell_bytes + a.identity_off + (uint32_t)i * W) = identity_vector<DT, W>();
 
         // ---- (1) load: cell i < n_in is the i-th loaded cell; its operand word comes straight from memory
         const int32_t in_lanes = b.n_in << ls, out_lanes = b.n_out << ls;
@@ -492,21 +505,22 @@ __global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
         const int32_t out_c0 = ok0 ? tab[b.off_out + 2 * (tid >> ls)] : 0;
         const int32_t out_w0 = ok0 ? tab[b.off_out + 2 * (tid >> ls) + 1] : 0;
         int32_t lo0 = level_first(levreg, 0, b.n_levels), lo1 = level_first(levreg, 1, b.n_levels);
+        const uint32_t voff = (uint32_t)(tid & vmask) * W;
         StagedTask cur;
-        fetch_task(cur, tab, b, lo0, lo1, tid, ls);
+        bool cur_on = false;
+        if (b.n_levels > 0) cur_on = fetch_task(cur, tab, b, lo0, lo1, tid, ls);
         for (int32_t lv = 0; lv < b.n_levels; lv++) {
             const int32_t lo2 = level_first(levreg, lv + 2, b.n_levels);
             StagedTask nxt;
-            fetch_task(nxt, tab, b, lo1, lo2, tid, ls);
-            if (live) run_task<DT, W>(cells, tab, b, cur, tid & vmask, ls);
+            const bool nxt_on = fetch_task(nxt, tab, b, lo1, lo2, tid, ls);
+            run_task<DT, W>(cell_bytes, tab, b, cur, cur_on, voff);
             const int32_t lanes = (lo1 - lo0) << ls;
             for (int32_t i = tid + BT; i < lanes; i += BT) {       // levels wider than the workgroup
-                if ((i & vmask) >= here) continue;
                 StagedTask t;
-                fetch_task(t, tab, b, lo0, lo1, i, ls);
-                run_task<DT, W>(cells, tab, b, t, i & vmask, ls);
+                const bool on = fetch_task(t, tab, b, lo0, lo1, i, ls);
+                run_task<DT, W>(cell_bytes, tab, b, t, on, (uint32_t)(i & vmask) * W);
             }
-            cur = nxt;
+            cur = nxt; cur_on = nxt_on;
             staged_sync(one_wave);
             lo0 = lo1; lo1 = lo2;
         }
@@ -519,7 +533,7 @@ __global__ void __launch_bounds__(1024) sccl_staged_kernel(const StagedArgs a) {
             const int32_t ow = base == 0 ? out_w0 : (ok ? tab[b.off_out + 2 * (i >> ls) + 1] : 0);
             char* p = rank_base(base_lo, base_hi, ow & OPERAND_RANK_MASK) +
                       (int64_t)(ow >> OPERAND_RANK_BITS) * a.chunk_bytes + slice_off + (int64_t)(i & vmask) * W;
-            if (ok) *(V*)p = cells[(oc << ls) + (i & vmask)];
+            if (ok) *(V*)p = *(const V*)(cell_bytes + (uint32_t)oc + (uint32_t)(i & vmask) * W);
         }
         if (item + gridDim.x < a.num_items) staged_sync(one_wave); // the next item overwrites the block and the cells
     }
@@ -768,6 +782,7 @@ static sccl_status_t launch_staged(const sccl_plan_t* plan, const int32_t* table
     args.log_slice = sg.log_slice_vectors;
     args.block_words = sg.max_block_words;
     args.cell_words_room = sg.cell_words_room;
+    args.identity_off = (uint32_t)(((int64_t)sg.max_chunk_cells << sg.log_slice_vectors) * plan->vector_bytes);
     for (int32_t n = 0; n < plan->P; n++) args.bufs[n] = (char*)rank_buffers[n];
     staged_fn fn = pick_staged_kernel(plan->dtype, plan->vector_bytes);
     hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3((unsigned)sg.threads), (size_t)sg.lds_bytes, (hipStream_t)stream, args);
@@ -815,7 +830,7 @@ struct ScratchWriteArgs {
     int32_t words[SCRATCH_WRITE_WORDS];
 };
 
-__global__ void __launch_bounds__(256) sccl_scratch_write_kernel(const ScratchWriteArgs a) {
+static __global__ void __launch_bounds__(256) sccl_scratch_write_kernel(const ScratchWriteArgs a) {
     for (int32_t i = (int32_t)threadIdx.x; i < a.count; i += 256) a.dst[i] = a.words[i];
 }
 

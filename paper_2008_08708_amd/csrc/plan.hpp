@@ -38,12 +38,17 @@ constexpr int32_t MAX_SLOTS = 1 << (31 - OPERAND_RANK_BITS);
 //           levels + 2            first task of every level, the end, the end again
 //           2 x stored cells      the cells to store at the end: the storage that holds the value, the cell's
 //                                 operand word; then padding to 4 words
-//           8 x tasks             per task: destination storage | k << 16 ; k == 0: the source storage of a copy,
-//                                 else the index of the task's fifth source in the overflow list ; the
-//                                 first four source cells in schedule order ; two words of padding
+//           8 x tasks             per task: destination storage | k << 24 ; the index of the task's fifth source in
+//                                 the overflow list ; four source storages in schedule order -- a copy (k == 0) has
+//                                 its source in the first, unused ones name the identity storage (one past the last
+//                                 real one; the kernel fills it with the additive identity) ; two words of padding
 //           overflow sources      fifth and later sources of reduce tasks with more than four; padding
+//   In the device table a storage is the BYTE offset of its slice in the workgroup's cell area (storage i starts at
+//   i * slice vectors * vector bytes).  The host-side pieces the table is made from keep storage ids, and their task
+//   records are: destination | k << 16 ; copy: the source, reduce: the overflow index ; the first four sources.
 constexpr int32_t STAGED_HEADER_WORDS = 8;
 constexpr int32_t STAGED_TASK_WORDS = 8;
+constexpr int32_t STAGED_TASK_K_SHIFT = 24;               // word 0 of a task record: destination byte offset | fan-in << 24
 constexpr int32_t STAGED_MAX_LEVELS = 256;                // a wavefront keeps the level table in four registers per lane
 constexpr int64_t STAGED_LDS_LIMIT = 160 * 1024;          // local data share of one gfx950 compute unit
 constexpr int64_t STAGED_AUTO_TINY_BYTES = 512ll << 10;   // all rank buffers together: launch overhead dominates
@@ -57,6 +62,9 @@ struct sccl_staged {
     int32_t n_cells = 0, n_in = 0, n_out = 0, n_levels = 0, staged_levels = 0, n_tasks = 0, max_level_tasks = 0;
     int32_t max_chunk_groups = 0;
     int32_t max_chunk_cells = 0, max_chunk_in = 0, max_chunk_out = 0, max_block_words = 0, cell_words_room = 0;
+    // per chunk, with storage ids; the device table is made from these once the slice length is known
+    struct Pieces { std::vector<int32_t> cell_word, out_cells, lev_first, tasks, extra; int32_t n_in = 0, n_levels = 0; };
+    std::vector<Pieces> pieces;
     std::vector<int32_t> table;
     // launch shape
     int32_t log_slice_vectors = 0;

@@ -66,7 +66,8 @@ def test_full_size_every_byte(label, wl):
     plan = sccl.sccl_plan_create(*sf.descriptions(wl.dtype, epc))
     st = sccl.sccl_plan_stats(plan)
     if label.startswith("cfg5-") and "latency" not in label:    # the measured crossover of the automatic lowering
-        want_lowering = sccl.SCCL_LOWER_STAGED if wl.bytes_per_rank <= (1 << 20) else sccl.SCCL_LOWER_MEMORY
+        staged_up_to = (4 << 20) if "allgather" in label else (1 << 20)
+        want_lowering = sccl.SCCL_LOWER_STAGED if wl.bytes_per_rank <= staged_up_to else sccl.SCCL_LOWER_MEMORY
         assert st["lowering"] == want_lowering, (wl.bytes_per_rank, st["lowering"])
     sccl.sccl_execute(plan, work)
     torch.cuda.synchronize()
