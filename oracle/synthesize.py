@@ -20,17 +20,16 @@ It is the "Boolean per tuple" encoding the paper found too slow for Z3 on its la
 for the small rows of its tables an MILP solver handles it in seconds.  The answer is exact:
 either a schedule (checked again by validate.py) or a proof that none exists.
 
-pareto_synthesize follows Algorithm 1: S from the diameter upwards, (R, C) with S <= R <= S + k
-and R/C >= b_l in ascending R/C, report the first feasible one per S, stop when R/C reaches b_l.
-One reading: as printed, the procedure would also report, at a larger S, an algorithm whose R/C is
-no better than one already found with fewer steps; such an algorithm is dominated (section 3.7's
-definition) and the paper's tables do not list any, so candidates that cannot improve on the best
-R/C found so far are skipped.
+pareto_frontier walks the Pareto frontier of (steps, bandwidth cost R/C) that Algorithm 1 reports:
+per step count, from the diameter upwards, the cheapest feasible R/C among S <= R <= S + k, until the
+bandwidth floor is met.  One reading: a point whose R/C is no better than one already found with
+fewer steps is dominated (section 3.7's definition) and the paper's tables list none, so only
+costs that improve on the best found so far are tried.
 """
 from __future__ import annotations
 
 from fractions import Fraction
-from typing import Callable, List, Optional, Sequence, Tuple
+from typing import Callable, Iterator, List, Optional, Sequence, Tuple
 
 import numpy as np
 from scipy.optimize import Bounds, LinearConstraint, milp
@@ -140,31 +139,46 @@ def _prune(sched: Schedule, coll: Collective) -> Schedule:
     return Schedule(sched.rounds, np.array(keep, dtype=np.int32).reshape(-1, 5))
 
 
+def frontier_candidates(S: int, k: int, floor: Fraction, beaten: Optional[Fraction]) -> List[Tuple[Fraction, int, int]]:
+    """The (R / C, R, C) a k-synchronous algorithm with S steps can have (S <= R <= S + k, R / C no lower than the
+    bandwidth floor) that would improve on the lowest bandwidth cost known at fewer steps, cheapest first."""
+    seen = {}
+    for R in range(S, S + k + 1):
+        C = 1
+        while Fraction(R, C) >= floor:
+            ratio = Fraction(R, C)
+            if beaten is None or ratio < beaten:
+                seen.setdefault(ratio, (ratio, R, C))              # the same cost with fewer rounds and chunks first
+            C += 1
+    return sorted(seen.values())
+
+
+def pareto_frontier(k: int, topo: Topology, make_collective: Callable[[int], Collective],
+                    bandwidth_bound: Optional[Fraction] = None, max_steps: int = 16,
+                    time_limit: float = 120.0) -> Iterator[Tuple[int, int, int, Schedule]]:
+    """The Pareto frontier of (steps S, bandwidth cost R / C) over k-synchronous schedules, one point per S, by
+    increasing S -- what Algorithm 1 of the paper reports, and the rows its Tables 4 and 5 mark as the frontier.
+
+    A point (S, R / C) is on the frontier when a schedule exists and none with at most S steps has a lower R / C.
+    S starts at the latency floor (the diameter) and the walk ends at the first point that meets the bandwidth
+    floor, which no later point can improve on.  make_collective(C) builds the instance for C chunks per node.
+    """
+    floor = bandwidth_bound if bandwidth_bound is not None else allgather_bandwidth_bound(topo)
+    beaten: Optional[Fraction] = None                               # lowest R / C of the points yielded so far
+    for S in range(diameter(topo), max_steps + 1):
+        for ratio, R, C in frontier_candidates(S, k, floor, beaten):
+            witness = solve_instance(topo, make_collective(C), S, R, time_limit)
+            if witness is None:
+                continue                                            # proved infeasible: try the next cheapest cost
+            yield C, S, R, witness
+            beaten = ratio
+            break
+        if beaten is not None and beaten == floor:
+            return
+
+
 def pareto_synthesize(k: int, topo: Topology, make_collective: Callable[[int], Collective],
                       bandwidth_bound: Optional[Fraction] = None, max_steps: int = 16,
                       time_limit: float = 120.0) -> List[Tuple[int, int, int, Schedule]]:
-    """Algorithm 1 of the paper.  make_collective(C) builds the instance for C chunks per node.
-
-    Returns the reported algorithms as (C, S, R, schedule), in the order found.
-    """
-    a_l = diameter(topo)
-    b_l = bandwidth_bound if bandwidth_bound is not None else allgather_bandwidth_bound(topo)
-    out = []
-    best = None                                         # lowest R/C reported so far
-    for S in range(a_l, max_steps + 1):
-        cands = []
-        for R in range(S, S + k + 1):
-            for C in range(1, int(Fraction(R) / b_l) + 1):
-                ratio = Fraction(R, C)
-                if ratio >= b_l and (best is None or ratio < best):
-                    cands.append((ratio, R, C))
-        cands.sort()
-        for ratio, R, C in cands:
-            found = solve_instance(topo, make_collective(C), S, R, time_limit)
-            if found is not None:
-                out.append((C, S, R, found))
-                best = ratio
-                if ratio == b_l:
-                    return out
-                break
-    return out
+    """All frontier points as a list of (C, S, R, schedule): see pareto_frontier."""
+    return list(pareto_frontier(k, topo, make_collective, bandwidth_bound, max_steps, time_limit))

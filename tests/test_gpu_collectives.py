@@ -232,3 +232,27 @@ def test_set_valued_bandwidth_constraints(which):
     assert_same_bits(want, got)
     for g in got[1:]:
         assert (bits(g) == bits(got[0])).all()
+
+
+def test_the_papers_table_rows_execute():
+    # every stored witness of Tables 4 and 5 (and the Allreduce composed from every Allgather witness) through the
+    # library on the GPU, under both lowerings, against the oracle
+    import glob
+    import os
+    from oracle import reproduce_tables as rt
+    topos = {"ring8": tp.ring(8), "dgx1": tp.dgx1()}
+    paths = sorted(glob.glob(os.path.join(rt.WITNESSES, "*.txt")))
+    assert len(paths) >= 36
+    for path in paths:
+        tname, name, C, S, R = os.path.basename(path)[:-4].split("_")
+        topo, coll = topos[tname], rt.MAKE[name](8, int(C))
+        sched = rt.read_witness(path)
+        epc = 4 * 19 + 4
+        bufs = poisoned(coll, "f32", "uniform", 71, epc)
+        want, got = run_both(topo, coll, sched, "f32", bufs, epc, label=os.path.basename(path))
+        assert_same_bits(want, got)
+        if name == "allgather":
+            ar, arc = gen.compose_allreduce(sched, coll)
+            rb = [inputs.generate("uniform", "f32", 73, n, 0, arc.num_chunks * epc) for n in range(8)]
+            want, got = run_both(topo, arc, ar, "f32", rb, epc, label="allreduce-of-" + os.path.basename(path))
+            assert_same_bits(want, got)
