@@ -305,11 +305,13 @@ sccl_status_t sccl_cost_fit(int32_t n, const double* a, const double* b, const d
  * The same fit with a constant term: least squares for t = t0 + a * alpha + b * beta, n >= 3.  On one GPU a
  * launch costs a few microseconds whatever the schedule, which the paper's two-term model (section 3.6) has no
  * place for; with t0 taken out, alpha and beta describe what a step and a byte add.  t0 does not change which of
- * several plans sccl_select_plan prefers; the alpha and beta fitted beside it do.  SCCL_ERR_INVALID_ARG if the
- * samples do not determine the three constants.
+ * several plans sccl_select_plan prefers; the alpha and beta fitted beside it do.  `weights` (n values >= 0, or
+ * NULL for all ones) scales each sample's residual: with weights 1 / t the fit minimises RELATIVE errors, so that
+ * the microsecond-sized samples near the crossover count as much as the millisecond-sized ones.
+ * SCCL_ERR_INVALID_ARG if the samples do not determine the three constants.
  */
-sccl_status_t sccl_cost_fit_intercept(int32_t n, const double* a, const double* b, const double* t, double* out_t0,
-                                      double* out_alpha, double* out_beta);
+sccl_status_t sccl_cost_fit_intercept(int32_t n, const double* a, const double* b, const double* t, const double* weights,
+                                      double* out_t0, double* out_alpha, double* out_beta);
 
 #ifdef __cplusplus
 }

@@ -49,12 +49,15 @@ sccl_status_t sccl_cost_fit(int32_t n, const double* a, const double* b, const d
     return SCCL_OK;
 }
 
-// Least squares for t_i = t0 + a_i * alpha + b_i * beta.  The three columns differ by many orders of magnitude
-// (1, steps, bytes), so each is scaled by its largest magnitude before the 3 x 3 normal equations are solved
-// by elimination with partial pivoting.
-sccl_status_t sccl_cost_fit_intercept(int32_t n, const double* a, const double* b, const double* t, double* out_t0,
-                                      double* out_alpha, double* out_beta) {
+// Weighted least squares for t_i = t0 + a_i * alpha + b_i * beta: minimises the sum of (w_i * residual_i)^2.  The
+// three columns differ by many orders of magnitude (1, steps, bytes), so each is scaled by its largest magnitude
+// before the 3 x 3 normal equations are solved by elimination with partial pivoting.
+sccl_status_t sccl_cost_fit_intercept(int32_t n, const double* a, const double* b, const double* t, const double* weights,
+                                      double* out_t0, double* out_alpha, double* out_beta) {
     if (n < 3 || !a || !b || !t || !out_t0 || !out_alpha || !out_beta) return SCCL_ERR_INVALID_ARG;
+    if (weights)
+        for (int32_t i = 0; i < n; i++)
+            if (!(weights[i] >= 0.0) || !std::isfinite(weights[i])) return SCCL_ERR_INVALID_ARG;
     double sa = 0, sb = 0;
     for (int32_t i = 0; i < n; i++) {
         if (!std::isfinite(a[i]) || !std::isfinite(b[i]) || !std::isfinite(t[i])) return SCCL_ERR_INVALID_ARG;
@@ -63,10 +66,11 @@ sccl_status_t sccl_cost_fit_intercept(int32_t n, const double* a, const double* 
     if (!(sa > 0) || !(sb > 0)) return SCCL_ERR_INVALID_ARG;
     double m[3][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
     for (int32_t i = 0; i < n; i++) {
-        const double x[3] = {1.0, a[i] / sa, b[i] / sb};
+        const double w = weights ? weights[i] : 1.0;
+        const double x[3] = {w, w * a[i] / sa, w * b[i] / sb};
         for (int r = 0; r < 3; r++) {
             for (int c = 0; c < 3; c++) m[r][c] += x[r] * x[c];
-            m[r][3] += x[r] * t[i];
+            m[r][3] += x[r] * w * t[i];
         }
     }
     for (int col = 0; col < 3; col++) {

@@ -132,7 +132,7 @@ def lib() -> ctypes.CDLL:
         L.sccl_cost_fit.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                     ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.sccl_cost_fit_intercept.restype = ctypes.c_int
-        L.sccl_cost_fit_intercept.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        L.sccl_cost_fit_intercept.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                               ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                               ctypes.POINTER(ctypes.c_double)]
         _lib = L
@@ -322,13 +322,18 @@ def sccl_cost_fit(a: Sequence[float], b: Sequence[float], t: Sequence[float]) ->
     return al.value, be.value
 
 
-def sccl_cost_fit_intercept(a: Sequence[float], b: Sequence[float], t: Sequence[float]) -> Tuple[float, float, float]:
-    """(t0, alpha, beta) of the least-squares fit t = t0 + a * alpha + b * beta."""
+def sccl_cost_fit_intercept(a: Sequence[float], b: Sequence[float], t: Sequence[float],
+                            weights: Optional[Sequence[float]] = None) -> Tuple[float, float, float]:
+    """(t0, alpha, beta) of the (weighted) least-squares fit t = t0 + a * alpha + b * beta."""
     aa, bb, tt = (np.ascontiguousarray(x, dtype=np.float64) for x in (a, b, t))
     if not (aa.shape == bb.shape == tt.shape and aa.ndim == 1):
         raise ValueError("a, b, t must be 1-d arrays of one length")
+    ww = None if weights is None else np.ascontiguousarray(weights, dtype=np.float64)
+    if ww is not None and ww.shape != aa.shape:
+        raise ValueError("weights must have the length of the samples")
     t0, al, be = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
-    st = lib().sccl_cost_fit_intercept(aa.size, aa.ctypes.data, bb.ctypes.data, tt.ctypes.data, ctypes.byref(t0),
+    st = lib().sccl_cost_fit_intercept(aa.size, aa.ctypes.data, bb.ctypes.data, tt.ctypes.data,
+                                       None if ww is None else ww.ctypes.data, ctypes.byref(t0),
                                        ctypes.byref(al), ctypes.byref(be))
     if st != SCCL_OK:
         raise ScclError(st, "sccl_cost_fit_intercept")

@@ -134,6 +134,13 @@ def test_fit_with_an_intercept_recovers_the_constants_and_matches_numpy():
     ref = np.linalg.lstsq(A, noisy, rcond=None)[0]
     assert g0 == pytest.approx(ref[0], rel=1e-6)
     assert ga == pytest.approx(ref[1] / a.max(), rel=1e-6) and gb == pytest.approx(ref[2] / b.max(), rel=1e-6)
+    # weights 1 / t: relative errors
+    g0, ga, gb = sccl.sccl_cost_fit_intercept(a, b, noisy, weights=1.0 / noisy)
+    ref = np.linalg.lstsq(A / noisy[:, None], np.ones_like(noisy), rcond=None)[0]
+    assert g0 == pytest.approx(ref[0], rel=1e-6)
+    assert ga == pytest.approx(ref[1] / a.max(), rel=1e-6) and gb == pytest.approx(ref[2] / b.max(), rel=1e-6)
+    with pytest.raises(sccl.ScclError):
+        sccl.sccl_cost_fit_intercept(a, b, noisy, weights=-np.ones_like(noisy))
     # with t0 = 0 in the data the two fits agree on alpha and beta
     al2, be2 = sccl.sccl_cost_fit(a, b, a * alpha + b * beta)
     z0, al3, be3 = sccl.sccl_cost_fit_intercept(a, b, a * alpha + b * beta)
