@@ -43,8 +43,30 @@ def bench_kernels():
         L.bench_stream.restype = ctypes.c_int
         L.bench_stream.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
                                    ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        L.bench_empty.restype = ctypes.c_int
+        L.bench_empty.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         _aid = L
     return _aid
+
+
+def launch_floor_us(grid=256, threads=64, reps=30):
+    """Median microseconds between two HIP events around a kernel that does nothing: what any single launch costs
+    on this machine before its work starts (the floor under every small-size figure)."""
+    import torch
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    s = torch.cuda.current_stream().cuda_stream
+    times = []
+    for r in range(reps + 3):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        if bench_kernels().bench_empty(grid, threads, ctypes.c_void_p(sink.data_ptr()), ctypes.c_void_p(int(s))) != 0:
+            raise RuntimeError("bench_empty failed")
+        b.record()
+        torch.cuda.synchronize()
+        if r >= 3:
+            times.append(a.elapsed_time(b) * 1e3)
+    times.sort()
+    return round(times[len(times) // 2], 2)
 
 
 STREAM_MODES = {"read": 0, "write": 1, "copy": 2, "fanout": 3, "fanin": 4}
@@ -504,7 +526,8 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     if args.ceilings:
-        print(json.dumps({"streaming_ceilings": stream_ceilings(), "peak_GBs": HBM_PEAK_GBS}), flush=True)
+        print(json.dumps({"streaming_ceilings": stream_ceilings(), "peak_GBs": HBM_PEAK_GBS,
+                          "empty_kernel_us_between_events": {str(g): launch_floor_us(g) for g in (64, 256, 4096, 16384, 65536)}}), flush=True)
         return
     options = {k: v for k, v in (("block_threads", args.block_threads), ("vectors_per_thread", args.vectors_per_thread),
                                  ("max_workgroups", args.max_workgroups), ("lowering", args.lowering),
@@ -563,6 +586,7 @@ def main():
         try:
             c = stream_ceilings(reps=4, grids=(1024, 2048))
             line["streaming_ceilings_gbs"] = {k: v["GBs"] for k, v in c.items()}
+            line["empty_kernel_us_between_events"] = launch_floor_us()
         except Exception as e:                    # measurement aid only
             line["streaming_ceilings_gbs"] = None
             print(f"streaming ceilings failed: {e}", file=sys.stderr)

@@ -68,9 +68,21 @@ __global__ void __launch_bounds__(256) bench_fanin_kernel(u4* __restrict__ dst, 
     }
 }
 
+// does nothing: what is measured around it is the launch itself
+__global__ void __launch_bounds__(256) bench_empty_kernel(uint32_t* sink) {
+    if (sink && threadIdx.x == 1000) sink[0] = 1;
+}
+
 }  // namespace
 
 extern "C" {
+
+// `grid` workgroups of `threads` lanes (64 .. 256) that do nothing.  Returns 0, -1 for a bad argument, -2 when the launch failed.
+int bench_empty(int grid, int threads, void* sink, void* stream) {
+    if (grid < 1 || threads < 64 || threads > 256) return -1;
+    hipLaunchKernelGGL(bench_empty_kernel, dim3(grid), dim3(threads), 0, (hipStream_t)stream, (uint32_t*)sink);
+    return hipGetLastError() == hipSuccess ? 0 : -2;
+}
 
 // mode 0: read `bytes` from src.  1: write `bytes` to dst.  2: copy `bytes`.  3: read `bytes` from src, write them
 // to k regions of dst, `bytes` apart.  4: read k regions of src, `bytes` apart, write their sum (`bytes`) to dst.

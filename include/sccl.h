@@ -272,6 +272,41 @@ sccl_status_t sccl_execute_static(const sccl_plan_t* plan, void* const* rank_buf
 /* S, R, k, group counts, algorithmic byte counts and the launch shape. */
 sccl_status_t sccl_plan_stats(const sccl_plan_t* plan, sccl_stats_t* out_stats);
 
+/*
+ * The compiled step table of a plan as 32-bit words: exactly what the kernel of the given lowering walks (and what
+ * sccl_execute_static writes into its array).  Host only; for inspection, and so that the plan compiler can be
+ * checked without a GPU by interpreting the table.  Copies at most `capacity` words into `out` (NULL allowed when
+ * capacity is 0); *out_words is always the table's length; info[0..3] describe it.  An operand is
+ * rank | chunk position << 8.  SCCL_ERR_INVALID_ARG for an unknown lowering or a staged table the plan does not have
+ * (sccl_stats_t.staged_available == 0).
+ *
+ * lowering == SCCL_LOWER_MEMORY.  info[0] = word at which the op lists start.  Words 0 .. G: for every chunk the
+ * offset of its op list relative to info[0], and the end.  An op list is the chunk's groups in step order, each
+ *     header   bit 0: 0 copy group, 1 reduce group; k << 8
+ *     anchor   copy: the source operand; reduce: the destination operand
+ *     k words  copy: the destination operands; reduce: the source operands in schedule order
+ * A copy group stores the anchor's chunk to every destination; a reduce group adds the sources, left to right, onto
+ * the destination's own value.
+ *
+ * lowering == SCCL_LOWER_STAGED.  info[0] = words per block (one block per chunk), info[1] = words reserved for
+ * storage operands, info[2] = log2 of the slice length in vectors, info[3] = byte offset of the identity storage.
+ * A workgroup keeps one slice (1 << info[2] vectors of sccl_stats_t.vector_bytes) of every "storage" of a chunk in
+ * its local data share, storage i at byte i * slice bytes; below, a storage is named by that byte offset.  Block:
+ *     8 words          storages, storages to load (the first ones), cells to store, levels, tasks, overflow words, 0, 0
+ *     info[1] words    the operand each storage is loaded from (meaningful for the storages to load)
+ *     levels + 2       index of the first task of every level, then the number of tasks, twice
+ *     2 x stores       for every cell the schedule wrote: the storage holding its final value, its operand
+ *     (padding to a multiple of 4 words)
+ *     8 x tasks        destination storage | k << 24, overflow index, four source storages, two words of padding.
+ *                      k == 0: a copy of the first source.  Otherwise the destination's own value plus the first
+ *                      min(k, 4) sources in order (unused ones name the identity storage, which holds the additive
+ *                      identity), plus overflow[index .. index + k - 5] for k > 4; written to the destination.
+ *     overflow words   fifth and later sources
+ * Tasks of one level touch no storage in conflicting ways; levels run in order; then the stores.
+ */
+sccl_status_t sccl_plan_table(const sccl_plan_t* plan, int32_t lowering, int32_t* out, int64_t capacity,
+                              int64_t* out_words, int32_t info[4]);
+
 /* Frees host and device memory of the plan; NULL is allowed.  The caller
  * makes sure no execute of this plan is still running. */
 void sccl_plan_destroy(sccl_plan_t* plan);

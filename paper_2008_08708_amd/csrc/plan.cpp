@@ -623,3 +623,25 @@ sccl_status_t sccl_compile_host(const sccl_topology_t* topo, const sccl_collecti
     st.static_table_bytes = 4 * (int64_t)(plan->lowering == SCCL_LOWER_STAGED ? sg.table.size() : plan->static_image.size());
     return SCCL_OK;
 }
+
+
+extern "C" sccl_status_t sccl_plan_table(const sccl_plan_t* plan, int32_t lowering, int32_t* out, int64_t capacity,
+                                         int64_t* out_words, int32_t info[4]) {
+    if (!plan || !out_words || !info || capacity < 0 || (capacity > 0 && !out)) return SCCL_ERR_INVALID_ARG;
+    const std::vector<int32_t>* table;
+    if (lowering == SCCL_LOWER_MEMORY) {
+        table = &plan->static_image;
+        info[0] = plan->static_prog_off; info[1] = info[2] = info[3] = 0;
+    } else if (lowering == SCCL_LOWER_STAGED && plan->staged.available) {
+        const sccl_staged& sg = plan->staged;
+        table = &sg.table;
+        info[0] = sg.max_block_words; info[1] = sg.cell_words_room; info[2] = sg.log_slice_vectors;
+        info[3] = (int32_t)(((int64_t)sg.max_chunk_cells << sg.log_slice_vectors) * plan->vector_bytes);
+    } else {
+        return SCCL_ERR_INVALID_ARG;
+    }
+    *out_words = (int64_t)table->size();
+    const int64_t n = std::min<int64_t>(capacity, (int64_t)table->size());
+    if (n > 0) std::memcpy(out, table->data(), (size_t)n * sizeof(int32_t));
+    return SCCL_OK;
+}

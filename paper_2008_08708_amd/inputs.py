@@ -13,6 +13,9 @@ Distributions
   uniform   fp32 in [-1, 1): (u24 / 2^23) - 1, exact in binary32
   smallint  integers in [-8, 8] (every partial sum of up to 2^10 of them is exact in fp16 and fp32)
   normal    N(0, 1) by Box-Muller in double, rounded once to the target dtype
+  wide      `uniform` scaled by an exact power of two, 2^-12 .. 2^12 (2^-14 .. 2^10 for fp16, whose sums are taken in
+            binary32 and round only when operands are 14 or more binades apart): neighbouring elements differ by many
+            binades, so many sums round and a sum taken in another order has other bits
 """
 from __future__ import annotations
 
@@ -62,6 +65,15 @@ def generate(dist: str, dtype: str, seed: int, rank: int, start: int, count: int
     if dist == "smallint":
         v = ((r >> np.uint64(40)) % np.uint64(17)).astype(np.int64) - 8
         return v.astype(npdt)
+    if dist == "wide":
+        if dtype == "i32":
+            raise ValueError("wide is a floating distribution")
+        u24 = (r >> np.uint64(40)).astype(np.float32)
+        if dtype == "f32":
+            e = ((r >> np.uint64(8)) % np.uint64(25)).astype(np.int32) - 12
+        else:
+            e = ((r >> np.uint64(8)) % np.uint64(25)).astype(np.int32) - 14
+        return np.ldexp(u24 * np.float32(2.0 ** -23) - np.float32(1.0), e).astype(npdt)
     if dist == "normal":
         r2 = raw64(seed, rank, start, count, stream=1)
         u1 = ((r >> np.uint64(11)).astype(np.float64) + 1.0) * (2.0 ** -53)      # (0, 1]

@@ -87,7 +87,7 @@ class sccl_stats_t(ctypes.Structure):
 
 
 EXPORTS = ["sccl_plan_create", "sccl_plan_create_ex", "sccl_execute", "sccl_execute_stepwise", "sccl_execute_memcpy",
-           "sccl_execute_static", "sccl_plan_stats", "sccl_plan_destroy",
+           "sccl_execute_static", "sccl_plan_stats", "sccl_plan_table", "sccl_plan_destroy",
            "sccl_status_string", "sccl_plan_cost", "sccl_select_plan", "sccl_cost_fit", "sccl_cost_fit_intercept"]
 
 _lib = None
@@ -119,6 +119,9 @@ def lib() -> ctypes.CDLL:
             fn.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p]
         L.sccl_plan_stats.restype = ctypes.c_int
         L.sccl_plan_stats.argtypes = [ctypes.c_void_p, ctypes.POINTER(sccl_stats_t)]
+        L.sccl_plan_table.restype = ctypes.c_int
+        L.sccl_plan_table.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
+                                      ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32)]
         L.sccl_plan_destroy.restype = None
         L.sccl_plan_destroy.argtypes = [ctypes.c_void_p]
         L.sccl_status_string.restype = ctypes.c_char_p
@@ -283,6 +286,20 @@ def sccl_plan_stats(plan: Plan) -> dict:
     if st != SCCL_OK:
         raise ScclError(st, "sccl_plan_stats")
     return s.as_dict()
+
+
+def sccl_plan_table(plan: Plan, lowering: int) -> Tuple[np.ndarray, List[int]]:
+    """(the step table of the given lowering as int32 words, its four info words)."""
+    words = ctypes.c_int64()
+    info = (ctypes.c_int32 * 4)()
+    st = lib().sccl_plan_table(plan.handle, int(lowering), None, 0, ctypes.byref(words), info)
+    if st != SCCL_OK:
+        raise ScclError(st, "sccl_plan_table")
+    out = np.zeros(max(1, words.value), dtype=np.int32)
+    st = lib().sccl_plan_table(plan.handle, int(lowering), out.ctypes.data, words.value, ctypes.byref(words), info)
+    if st != SCCL_OK:
+        raise ScclError(st, "sccl_plan_table")
+    return out[:words.value], [int(x) for x in info]
 
 
 def sccl_plan_destroy(plan: Plan) -> None:

@@ -154,6 +154,19 @@ def test_addition_order_inside_a_group_is_the_schedules():
     assert outs[0] == np.float32(0.0) and outs[1] == np.float32(2.0 ** -23)
 
 
+@pytest.mark.parametrize("dtype,epc", [("f32", 2048 + 4 * 3), ("f16", 4096 + 8 * 5)])
+def test_wide_range_inputs_where_every_order_of_additions_has_other_bits(dtype, epc):
+    # neighbouring elements differ by up to 24 binades (12 for fp16): almost every partial sum rounds, so any change
+    # of the order of additions -- inside a group or across the levels of a chunk's tree -- changes bits somewhere
+    for topo, C, kind in ((tp.torus2d(4, 4), 4, "greedy"), (tp.hcm8(), 1, "greedy"), (tp.ring(8), 2, "ring")):
+        sched, coll = allreduce_of(topo, C, kind)
+        bufs = host_inputs("wide", dtype, 29, topo.num_nodes, coll.num_chunks, epc)
+        want, got = run_both(topo, coll, sched, dtype, bufs, epc, label=f"wide-{topo.name}-{dtype}")
+        assert_same_bits(want, got)
+        for g in got[1:]:
+            assert (bits(g) == bits(got[0])).all()
+
+
 def test_fp16_rounding_points_and_special_values():
     t = tp.complete(3)
     ar = col.allreduce(3, 1)
