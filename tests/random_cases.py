@@ -32,6 +32,8 @@ def random_case(seed):
     C = int(rng.integers(1, 4))
     what = ["allgather", "allreduce", "reducescatter", "broadcast", "alltoall", "gather"][int(rng.integers(0, 6))]
     dtype, dist = [("f32", "uniform"), ("f16", "normal"), ("i32", "u32")][int(rng.integers(0, 3))]
+    if dtype == "f32" and seed % 2:
+        dist = "wide"                                           # sums that round: the order of additions shows in the bits
     epc = int([1, 3, 16, 257, 1024, 2048 + 4 * int(rng.integers(0, 64)), 3 * 4096 + 8 * int(rng.integers(0, 64))][int(rng.integers(0, 7))])
     ag = col.allgather(P, C)
     rounds = [int(rng.integers(1, 3)) for _ in range(4)]        # some steps get two rounds
