@@ -124,3 +124,24 @@ def test_repeated_calls_on_one_stream_and_bad_buffers():
     torch.cuda.synchronize()
     sccl.sccl_plan_destroy(pa)
     sccl.sccl_plan_destroy(pb)
+
+
+def test_large_slices_through_the_static_entry_point():
+    """A host-only staged plan whose workgroups need 128 KiB of the local data share (more than a kernel gets without
+    asking): the static entry point has to ask for it itself, since the plan's creation never touched the device."""
+    import torch
+    sf = schedule_file.load("cfg3_allreduce_hcm8")
+    epc = 4 * (3 * 1024 + 17)
+    host = [inputs.generate("wide", "f32", 211, n, 0, 8 * epc) for n in range(8)]
+    want = [h.copy() for h in host]
+    ex.execute("f32", 8, epc, Schedule(sf.rounds, sf.sends), want)
+    plan = sccl.sccl_plan_create(*sf.descriptions("f32", epc), options={"flags": sccl.SCCL_PLAN_HOST_ONLY, "lowering": S,
+                                                                         "slice_vectors": 1024})
+    assert sccl.sccl_plan_stats(plan)["staged_lds_bytes"] > 64 * 1024
+    got = [torch.from_numpy(h.copy()).cuda() for h in host]
+    print("[case] static entry point, 128 KiB of local data share", flush=True)
+    sccl.sccl_execute_static(plan, got)
+    torch.cuda.synchronize()
+    for n in range(8):
+        assert (bits(got[n].cpu().numpy()) == bits(want[n])).all(), f"rank {n}"
+    sccl.sccl_plan_destroy(plan)
