@@ -36,8 +36,9 @@ def bench_kernels():
     global _aid
     if _aid is None:
         path = os.path.join(ROOT, "libbench_kernels.so")
-        if not os.path.exists(path):
-            raise RuntimeError(f"{path} is missing: build it with __graft_entry__.build()")
+        if not os.path.exists(path):                          # nothing built yet: build once, in-tree
+            from paper_2008_08708_amd import build as _build
+            _build.build_bench_kernels()
         import torch  # noqa: F401  (one HIP runtime per process: torch's, loaded first)
         L = ctypes.CDLL(path)
         L.bench_stream.restype = ctypes.c_int

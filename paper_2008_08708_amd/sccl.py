@@ -94,12 +94,18 @@ _lib = None
 
 
 def lib() -> ctypes.CDLL:
-    """The loaded library; raises if it has not been built (there is no fallback)."""
+    """The loaded library.  What is built in-tree is loaded as it is; only when nothing is there is it compiled
+    first.  There is no fallback: without the library every call raises."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2008_08708_amd.build` "
-                               "(or __graft_entry__.build()); this package has no CPU fallback")
+        if not os.path.exists(LIB_PATH):                      # nothing built yet: build once, in-tree
+            try:
+                from . import build as _build
+                _build.build_library()
+            except Exception as e:
+                raise RuntimeError(f"{LIB_PATH} is missing and could not be built ({e}): run `python -m "
+                                   "paper_2008_08708_amd.build` (or __graft_entry__.build()); this package has no "
+                                   "CPU fallback") from e
         # torch first: it brings its own copy of the HIP runtime (same soname as the system's), and the
         # process must hold exactly one -- the one torch allocates device memory and streams with.
         # Loaded after torch, this library's dependency resolves to that already-loaded runtime.
