@@ -323,6 +323,9 @@ __global__ void __launch_bounds__(256) sccl_step_kernel(const StepArgs a) {
 // the slice of every cell the schedule wrote.  Per element the operations and their order are those of the
 // schedule, so the bits equal the other lowerings'.  A chunk's chain of sends costs local-memory latency
 // per level instead of a cache round trip per group, which is what small buffers are bound by.
+// The plan compiler has already propagated copies (a cell that only receives a copy of a value that stays put is
+// stored straight from the storage holding that value: plan.cpp), so the levels that arrive here are the reduce
+// groups and the few copies that could not be propagated; a non-combining collective arrives with none.
 struct StagedArgs {
     const int32_t* table;         // one block per chunk, see plan.hpp
     int64_t chunk_bytes;
