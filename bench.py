@@ -375,7 +375,7 @@ def report(path, torch, workloads, sccl):
     from paper_2008_08708_amd.sccl import SCCL_LOWER_MEMORY, SCCL_LOWER_STAGED, ScclError
     rows = []
     names = [(k, workloads.WORKLOADS[k]) for k in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg4b", "alltoall", "broadcast", "reduce",
-                                                   "gather", "scatter")]
+                                                   "gather", "scatter", "reducescatter")]
     for coll in ("allgather", "allreduce"):
         for size in workloads.sweep_sizes():
             names.append((f"cfg5 {coll} {size}", workloads.sweep_workload(coll, size)))

@@ -122,6 +122,11 @@ def extra_configurations():
     out["gather_dgx1"] = (t, ga, gen.greedy_route(t, ga))
     sc = col.scatter(8, 8, 0)
     out["scatter_dgx1"] = (t, sc, gen.greedy_route(t, sc))
+    # Reducescatter, the inverse of an Allgather (section 3.5): the paper's DGX-1 Allgather row (2,3,3) inverted,
+    # (16,3,3) in its Table 4 footnote's counting (C times 8), on the reversed graph (the same graph: it is symmetric)
+    ag = col.allgather(8, 2)
+    rs, rsc = gen.reducescatter_from(syn.solve_instance(t, ag, 3, 3), ag)
+    out["reducescatter_dgx1"] = (t.reversed(), rsc, rs)
     return out
 
 

@@ -43,6 +43,8 @@ WORKLOADS: Dict[str, Workload] = {
     "reduce": Workload("reduce", "reduce_dgx1", "f32", "uniform", 8, 64 * MiB, False),
     "gather": Workload("gather", "gather_dgx1", "f32", "uniform", 9, 64 * MiB, True),
     "scatter": Workload("scatter", "scatter_dgx1", "f32", "uniform", 10, 64 * MiB, True),
+    # and Reducescatter, the inverted Allgather (2,3,3) of the paper's Table 4, 16 chunks of 16 MiB per rank
+    "reducescatter": Workload("reducescatter", "reducescatter_dgx1", "f32", "uniform", 11, 256 * MiB, False),
 }
 
 

@@ -37,7 +37,7 @@ ORACLE_SECONDS = 10.0                                            # oracle time p
 RANGE_BYTES = 32 << 20                                           # one range over all ranks and chunk positions: cache sized
 
 CASES = [(k, workloads.WORKLOADS[k]) for k in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg4b", "alltoall", "broadcast", "reduce",
-                                               "gather", "scatter")]
+                                               "gather", "scatter", "reducescatter")]
 for coll in ("allgather", "allreduce"):
     for size in workloads.sweep_sizes():                         # all eleven sizes of configuration 5
         CASES.append((f"cfg5-{coll}-{size}", workloads.sweep_workload(coll, size)))
@@ -129,7 +129,7 @@ def test_full_size_every_byte(label, wl):
         for n in range(1, P):
             assert torch.equal(work[n].view(tu), work[0].view(tu)), f"rank {n} differs from rank 0"
         assert not torch.isnan(work[0]).any()
-    else:                                                  # Reduce: no NaN where post puts the sum
+    else:                                                  # Reduce, Reducescatter: no NaN where post puts the sum
         for c in range(G):
             for n in range(P):
                 if sf.post[c, n]:

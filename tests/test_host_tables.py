@@ -140,7 +140,7 @@ def check(topo, coll, sched, dtype, dist, epc, seed=5, slot=None, slots_per_rank
 
 SCHEDULES = ["cfg1_allgather_ring4", "cfg2_allgather_hcm8", "cfg3_allreduce_hcm8", "cfg4_allreduce_ring8", "cfg5_allgather_torus4x4",
              "cfg5_allreduce_torus4x4", "cfg5_allreduce_torus4x4_latency", "alltoall_dgx1", "broadcast_dgx1", "reduce_dgx1",
-             "gather_dgx1", "scatter_dgx1"]
+             "gather_dgx1", "scatter_dgx1", "reducescatter_dgx1"]
 
 
 @pytest.mark.parametrize("name", SCHEDULES)
