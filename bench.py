@@ -186,13 +186,15 @@ _flush = None
 
 
 def flush_caches():
-    """Overwrites 1 GiB of scratch memory: whatever the L2s (8 x 4 MiB) and the memory-side cache (256 MiB) held of
-    the working set is gone afterwards.  Enqueued on the current stream, outside every timed window."""
+    """READS 1 GiB of scratch memory: whatever the L2s (8 x 4 MiB) and the memory-side cache (256 MiB) held of the
+    working set is evicted (and, where dirty, written back) before the timed launch starts, and what replaces it is
+    clean -- a flush that wrote would leave its own dirty lines to be written back during the timed launch.
+    Enqueued on the current stream, outside every timed window."""
     global _flush
     import torch
     if _flush is None:
-        _flush = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
-    bench_stream("write", _flush, None, 1 << 30, grid=1024)
+        _flush = (torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0"), torch.zeros(1, dtype=torch.int32, device="cuda:0"))
+    bench_stream("read", None, _flush[0], 1 << 30, grid=1024, sink=_flush[1])
 
 
 def time_workload(wl, steps, warmup, options=None, keep=False, mode="sccl_execute", cold=False):
@@ -503,7 +505,7 @@ def main():
     ap.add_argument("--slice-vectors", type=int, default=0)
     ap.add_argument("--staged-threads", type=int, default=0)
     ap.add_argument("--cold", action="store_true",
-                    help="flush the caches (a 1 GiB scratch write) between restoring the inputs and every timed launch")
+                    help="flush the caches (a 1 GiB scratch read) between restoring the inputs and every timed launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the plain streaming kernels")
     ap.add_argument("--ceilings", action="store_true", help="only measure the plain streaming kernels; one JSON line")
@@ -568,7 +570,7 @@ def main():
         "roofline": roofline(wl.name, st, mean_ms),
     }
     if not args.cold and not args.no_ceilings:
-        # the same kernel with cold caches (untimed region: restore + 1 GiB scratch write), a few steps
+        # the same kernel with cold caches (untimed region: restore + 1 GiB scratch read), a few steps
         for w, p in zip(run["work"], run["pristine"]):
             w.copy_(p)
         cold = []
