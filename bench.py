@@ -197,15 +197,23 @@ def flush_caches():
     bench_stream("read", None, _flush[0], 1 << 30, grid=1024, sink=_flush[1])
 
 
-def time_workload(wl, steps, warmup, options=None, keep=False, mode="sccl_execute", cold=False):
+def time_workload(wl, steps, warmup, options=None, keep=False, mode="sccl_execute", cold=False, cold_steps=0, memory=None):
     """Returns dict with per-step kernel times (ms) measured by events on the launch stream.  cold: the caches are
-    flushed between restoring the inputs and the timed launch (else the restore's writes may still sit in them)."""
+    flushed between restoring the inputs and the timed launch (else the restore's writes may still sit in them).
+    cold_steps: that many further launches with flushed caches ON THE SAME BUFFERS ("ms_cold"): a new allocation
+    gets other physical pages, which alone moves the largest workloads by several percent either way.
+    memory: (pristine, work) of an earlier run of the same sizes, to be used again for the same reason."""
     import torch
     from paper_2008_08708_amd import schedule_file, sccl
     dev = torch.device("cuda:0")
     sf = schedule_file.load(wl.schedule)
     pristine, epc = make_inputs(wl, sf, dev)
-    work = [torch.empty_like(b) for b in pristine]
+    if memory is None:
+        work = [torch.empty_like(b) for b in pristine]
+    else:
+        for old, new in zip(memory[0], pristine):
+            old.copy_(new)
+        pristine, work = memory
     plan = sccl.sccl_plan_create(*sf.descriptions(wl.dtype, epc), options=options)
     stats = sccl.sccl_plan_stats(plan)
     stream = torch.cuda.current_stream()
@@ -233,6 +241,17 @@ def time_workload(wl, steps, warmup, options=None, keep=False, mode="sccl_execut
     wall = time.perf_counter() - t0
     ms = [a.elapsed_time(b) for a, b in evs]
     out = {"ms": ms, "wall_s": wall, "stats": stats, "sf": sf, "epc": epc}
+    if cold_steps:
+        cevs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(cold_steps)]
+        for a, b in cevs:
+            restore()
+            if not cold:
+                flush_caches()
+            a.record(stream)
+            execute(plan, work, stream)
+            b.record(stream)
+        torch.cuda.synchronize()
+        out["ms_cold"] = [a.elapsed_time(b) for a, b in cevs]
     if keep:
         out.update({"pristine": pristine, "work": work, "plan": plan})
     else:
@@ -382,10 +401,13 @@ def report(path, torch, workloads, sccl):
         for size in workloads.sweep_sizes():
             names.append((f"cfg5 {coll} {size}", workloads.sweep_workload(coll, size)))
 
-    def median_us(w, steps, mode, opts=None, cold=False):
-        r = time_workload(w, steps, 3, options=opts, mode=mode, cold=cold)
+    def median_us(w, steps, mode, opts=None, cold_steps=0):
+        r = time_workload(w, steps, 3, options=opts, mode=mode, cold_steps=cold_steps)
         m = sorted(r["ms"])
         out = (m[len(m) // 2] * 1e3, m[0] * 1e3, r["stats"])
+        if cold_steps:
+            mc = sorted(r["ms_cold"])
+            out += (mc[len(mc) // 2] * 1e3,)
         del r
         torch.cuda.empty_cache()
         return out
@@ -393,8 +415,8 @@ def report(path, torch, workloads, sccl):
     fmt = lambda x: "-" if x is None else format(x, ".1f")
     for label, w in names:
         steps = 5 if w.bytes_per_rank >= (1 << 30) else 20
-        med, mn, s = median_us(w, steps, "sccl_execute")                     # the default: lowering chosen by the plan
-        cold_med = median_us(w, steps, "sccl_execute", cold=True)[0]
+        # the default (lowering chosen by the plan), then cold caches on the same buffers
+        med, mn, s, cold_med = median_us(w, steps, "sccl_execute", cold_steps=steps)
         mem_med = med if s["lowering"] == SCCL_LOWER_MEMORY else median_us(w, steps, "sccl_execute", {"lowering": SCCL_LOWER_MEMORY})[0]
         stg_med = None
         if s["lowering"] == SCCL_LOWER_STAGED:
@@ -418,15 +440,18 @@ def report(path, torch, workloads, sccl):
         rf = roofline(w.name, s, med * 1e-3)
         rows.append((label, s["num_nodes"], w.bytes_per_rank, s["chunk_bytes"], s["num_steps"], s["bytes_min"],
                      med, mn, s["bytes_min"] / (med * 1e-6) / 1e9, "staged" if s["lowering"] == SCCL_LOWER_STAGED else "memory",
-                     s["num_levels"], s["grid_workgroups"], mem_med, stg_med, step_med, cpy_med, graph_us, oracle, cold_med, rf))
+                     f'{s["num_levels"]} ({s["staged_levels"]})', s["grid_workgroups"], mem_med, stg_med, step_med, cpy_med, graph_us, oracle, cold_med, rf))
         print(f"[report] {label}: default ({rows[-1][9]}) {med:.1f} us warm, {cold_med:.1f} us cold ({rows[-1][8]:.1f} GB/s), "
               f"through memory {fmt(mem_med)} us, staged {fmt(stg_med)} us, per-step kernels {fmt(step_med)} us, "
               f"per-send copies {fmt(cpy_med)} us, in a graph of 20 {fmt(graph_us)} us each", file=sys.stderr, flush=True)
     os.makedirs(os.path.dirname(os.path.abspath(path)), exist_ok=True)
     with open(path, "w") as f:
+        f.write("`python bench.py --report FILE` on one MI355X (3 warm-up + 20 timed launches per figure, 5 at 16 GiB): every workload under the default lowering, warm and "
+                "with cold caches, each lowering forced, the paper's other two lowerings, and the oracle on the host.  Medians of "
+                "the time between HIP events around one execute call, microseconds.\n\n")
         f.write("| workload | P | bytes/rank | chunk bytes | S | bytes_min | sccl_execute: median us | min us | cold caches: median us "
                 "| effective GB/s | algorithmic % of 8 TB/s | compulsory % of 8 TB/s "
-                "| lowering | levels | grid | through memory: us | staged: us | one kernel per step: us | one copy per send: us "
+                "| lowering | dependency levels (left when staged) | grid | through memory: us | staged: us | one kernel per step: us | one copy per send: us "
                 "| each of 20 in one HIP graph: us | oracle on the host cores: GB/s (cores) | oracle on one core: GB/s "
                 "| full buffers bitwise equal to the oracle's |\n")
         f.write("|" + "---|" * 23 + "\n")
@@ -447,12 +472,19 @@ def report(path, torch, workloads, sccl):
             meas = []
             for size in workloads.sweep_sizes():
                 pair = []
+                memory = None                                      # both algorithms run in the same device memory
                 for alg in ("latency", "bandwidth"):
                     w = workloads.sweep_workload(coll, size, alg)
                     steps = 5 if size >= (1 << 30) else 20
-                    med, _, st_ = median_us(w, steps, "sccl_execute")
+                    r = time_workload(w, steps, 3, keep=True, memory=memory)
+                    memory = (r["pristine"], r["work"])
+                    sccl.sccl_plan_destroy(r["plan"])
+                    m, st_ = sorted(r["ms"]), r["stats"]
                     # the model's two coordinates: a = S, b = (R / C) * L = R * chunk bytes
-                    pair.append((med * 1e-6, float(st_["num_steps"]), float(st_["num_rounds"]) * st_["chunk_bytes"]))
+                    pair.append((m[len(m) // 2] * 1e-3, float(st_["num_steps"]), float(st_["num_rounds"]) * st_["chunk_bytes"]))
+                    del r
+                del memory
+                torch.cuda.empty_cache()
                 meas.append((size, pair))
             a = [p[1] for _, pair in meas for p in pair]
             b = [p[2] for _, pair in meas for p in pair]
