@@ -145,3 +145,23 @@ def test_large_slices_through_the_static_entry_point():
     for n in range(8):
         assert (bits(got[n].cpu().numpy()) == bits(want[n])).all(), f"rank {n}"
     sccl.sccl_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("seed", list(range(100, 140)))
+def test_random_cases_through_the_static_entry_point(seed):
+    """Random topologies, collectives, element types and ragged sizes (tests/random_cases.py), one after the other
+    through the one shared table, each under both lowerings with host-only plans: tables of every length follow each
+    other in the static array."""
+    from gpu_util import assert_same_bits, run_both
+    from random_cases import random_case
+    from test_random_schedules import make_inputs
+    label, topo, coll, sched, dtype, dist, epc = random_case(seed)
+    bufs = make_inputs(coll, dtype, dist, seed, epc)
+    for lowering in (M, S):
+        try:
+            want, got = run_both(topo, coll, sched, dtype, bufs, epc, label=label, mode="sccl_execute_static",
+                                 options={"lowering": lowering, "flags": sccl.SCCL_PLAN_HOST_ONLY})
+        except sccl.ScclError as e:
+            assert lowering == S and e.name == "SCCL_ERR_INVALID_ARG", (label, e.name)   # the cells do not fit the local data share
+            continue
+        assert_same_bits(want, got)
