@@ -165,3 +165,53 @@ def test_random_cases_through_the_static_entry_point(seed):
             assert lowering == S and e.name == "SCCL_ERR_INVALID_ARG", (label, e.name)   # the cells do not fit the local data share
             continue
         assert_same_bits(want, got)
+
+
+@pytest.mark.parametrize("lowering", [M, S])
+def test_static_entry_point_under_graph_capture(lowering):
+    """The table writes are kernels whose arguments hold the table words, so a captured call carries its own table:
+    replays are right although another plan's table was written into the shared array in between."""
+    import torch
+    from gpu_util import assert_same_bits, host_inputs
+    from helpers import to_binding
+    from oracle import collective as col, generate as gen, topology as tp
+    topo = tp.torus2d(4, 4)
+    ag = col.allgather(16, 2)
+    sched, coll = gen.compose_allreduce(gen.greedy_bfs(topo, ag), ag)
+    P, G, epc = 16, coll.num_chunks, 4 * 1031
+    plan = sccl.sccl_plan_create(*to_binding(topo, coll, sched, "f32", epc),
+                                 options={"lowering": lowering, "flags": sccl.SCCL_PLAN_HOST_ONLY})
+    small = schedule_file.load("cfg1_allgather_ring4")
+    other = sccl.sccl_plan_create(*small.descriptions("i32", 700), options={"flags": sccl.SCCL_PLAN_HOST_ONLY})
+    hb = [inputs.generate("u32", "i32", 8, n, 0, 4 * 700) for n in range(4)]
+    db = [torch.from_numpy(h.copy()).cuda() for h in hb]
+    pristine = [torch.zeros(G * epc, dtype=torch.float32, device="cuda") for _ in range(P)]
+    work = [torch.empty_like(p) for p in pristine]
+    print(f"[case] static entry point under graph capture, lowering={lowering}", flush=True)
+    sccl.sccl_execute_static(other, db)                    # the first call on the device happens outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for w, p in zip(work, pristine):
+            w.copy_(p)
+        sccl.sccl_execute_static(plan, work, side)
+    for seed in (5, 6, 7):
+        bufs = host_inputs("wide", "f32", seed, P, G, epc)
+        want = [b.copy() for b in bufs]
+        ex.execute("f32", G, epc, sched, want)
+        for p, b in zip(pristine, bufs):
+            p.copy_(torch.from_numpy(b))
+        sccl.sccl_execute_static(other, db)                # another table goes through the shared array
+        torch.cuda.synchronize()
+        print(f"[case]   replay seed={seed}", flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_same_bits(want, [w.cpu().numpy() for w in work])
+    for n in range(4):
+        g = db[n].cpu().numpy()
+        for c in range(4):
+            assert (g[c * 700:(c + 1) * 700] == hb[c % 4][c * 700:(c + 1) * 700]).all()
+    del graph
+    sccl.sccl_plan_destroy(plan)
+    sccl.sccl_plan_destroy(other)
