@@ -207,6 +207,8 @@ def time_workload(wl, steps, warmup, options=None, keep=False, mode="sccl_execut
     from paper_2008_08708_amd import schedule_file, sccl
     dev = torch.device("cuda:0")
     sf = schedule_file.load(wl.schedule)
+    if wl.options:                                   # the workload's own launch shape, unless the caller names one
+        options = {**wl.options, **(options or {})}
     pristine, epc = make_inputs(wl, sf, dev)
     if memory is None:
         work = [torch.empty_like(b) for b in pristine]
@@ -368,7 +370,7 @@ def crossover(steps, warmup):
         unit = sf.num_nodes * sf.positions_per_rank * 16                       # one 16-byte vector per chunk position
         for total in [1 << e for e in range(16, 29, 2)]:
             per_rank = max(1, total // unit) * sf.positions_per_rank * 16
-            w = dataclasses.replace(wl, bytes_per_rank=per_rank)
+            w = dataclasses.replace(wl, bytes_per_rank=per_rank, options=None)      # the plan's own launch shape at every size
             res = {}
             for key, low in (("auto", 0), ("memory", 1), ("staged", 2)):
                 try:

@@ -1,4 +1,5 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times (default options): every
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times (the plan's own choice, or the workload's
+stored launch shape where it has one): every
 configuration of the measurement -- configurations 1, 2, 3, 4 (both readings), all eleven sizes of configuration 5
 for both collectives, the latency-optimal torus pair, and Alltoall, Broadcast, Reduce, Gather, Scatter.
 
@@ -63,7 +64,7 @@ def test_full_size_every_byte(label, wl):
     P, G, K = sf.num_nodes, sf.num_chunks, sf.positions_per_rank
     pristine, epc = make_inputs(wl, sf, torch.device("cuda:0"))
     work = [p.clone() for p in pristine]
-    plan = sccl.sccl_plan_create(*sf.descriptions(wl.dtype, epc))
+    plan = sccl.sccl_plan_create(*sf.descriptions(wl.dtype, epc), options=wl.options)
     st = sccl.sccl_plan_stats(plan)
     if label.startswith("cfg5-") and "latency" not in label:    # the measured crossover of the automatic lowering
         staged_up_to = (4 << 20) if "allgather" in label else (1 << 20)
