@@ -258,13 +258,16 @@ sccl_status_t sccl_execute_memcpy(const sccl_plan_t* plan, void* const* rank_buf
  * table of the plan's lowering is larger than the array (sccl_stats_t.static_table_bytes says how large it is);
  * (2) checks the buffers like sccl_execute; (3) writes the table into the array with small kernels enqueued on
  * `stream`, one per 3.5 KiB of table (the words travel as kernel arguments: no copy from host memory and no
- * staging buffer is involved), on every call, because the array keeps whatever the last call left there;
- * (4) enqueues the plan's kernel on `stream`.  It calls no hipMalloc, no hipFree, no memset and no routine that
- * allocates, and does not synchronise.  The launch shape is sized for the current device.
+ * staging buffer is involved) -- the array keeps whatever the last call left there, so this is skipped only
+ * when the last call on this GPU was for the same plan; (4) enqueues the plan's kernel on `stream`.  It calls
+ * no hipMalloc, no hipFree, no memset and no routine that allocates, and does not synchronise.  The launch
+ * shape is sized for the current device.
  *
  * All calls on one GPU share the one array: calls on different streams, or from different threads, whose
  * work may overlap on the GPU race for it.  Serialise them on one stream (or with events).  Under graph
- * capture the table writes are captured too, by value, so a replay is correct whatever ran in between.
+ * capture the table writes are captured too, by value, so a replay is correct whatever ran in between; and
+ * because a replay rewrites the array at a time the library cannot see, from the first call on a capturing
+ * stream on every call on that GPU writes its table, captured or not.
  */
 #define SCCL_STATIC_SCRATCH_BYTES (256 * 1024)
 sccl_status_t sccl_execute_static(const sccl_plan_t* plan, void* const* rank_buffers, void* stream);

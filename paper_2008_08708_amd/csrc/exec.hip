@@ -27,6 +27,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdint>
 #include <cstring>
 #include <mutex>
@@ -649,6 +650,8 @@ sccl_status_t sccl_plan_create_ex(const sccl_topology_t* topology, const sccl_co
         st = SCCL_ERR_NOMEM;
     }
     if (st != SCCL_OK) { delete plan; return st; }
+    static std::atomic<uint64_t> next_plan_id{1};
+    plan->id = next_plan_id.fetch_add(1, std::memory_order_relaxed);
     if (!host_only) {
         plan->device = dev;
         plan->num_cus = num_cus;
@@ -841,6 +844,13 @@ constexpr int MAX_STATIC_DEVICES = 64;
 struct StaticDevice {
     int32_t* ptr = nullptr;                               // device address of `scratch` on this GPU
     int num_cus = 0;
+    // Whose table the array holds once everything enqueued so far has run (0: unknown).  Calls are required to be
+    // serialised on the GPU, so a call for the same plan need not write the table again.  That bookkeeping is
+    // only sound while every write of the array is a call the library sees: a captured call writes it again at
+    // every replay of its graph, whenever the caller chooses, so after the first call on a capturing stream
+    // (`captured`) nothing is assumed any more and every call writes its table.
+    uint64_t resident = 0;
+    bool captured = false;
 };
 static StaticDevice static_devices[MAX_STATIC_DEVICES];
 static std::mutex static_mutex;
@@ -876,9 +886,15 @@ sccl_status_t sccl_execute_static(const sccl_plan_t* plan, void* const* rank_buf
         return SCCL_ERR_DEVICE;
     }
 
-    // The table first, on the same stream, every time: the array is shared by every call on this GPU (and by
-    // replays of graphs that captured one), so nothing can be assumed about what it holds.
-    {
+    // The table first, on the same stream, unless the array is known to hold it already (see StaticDevice).
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing((hipStream_t)stream, &capture) != hipSuccess) {
+        (void)hipGetLastError();                          // e.g. the null stream while another stream captures
+        capture = hipStreamCaptureStatusActive;           // assume the worst
+    }
+    if (capture != hipStreamCaptureStatusNone) sd.captured = true;
+    if (sd.captured || sd.resident != plan->id) {
+        sd.resident = 0;
         ScratchWriteArgs w;
         for (size_t at = 0; at < image.size(); at += SCRATCH_WRITE_WORDS) {
             const size_t n = std::min(image.size() - at, (size_t)SCRATCH_WRITE_WORDS);
@@ -888,6 +904,7 @@ sccl_status_t sccl_execute_static(const sccl_plan_t* plan, void* const* rank_buf
             hipLaunchKernelGGL(sccl_scratch_write_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, w);
             if (hipGetLastError() != hipSuccess) return SCCL_ERR_DEVICE;
         }
+        if (!sd.captured) sd.resident = plan->id;
     }
     sccl_status_t st;
     if (staged) {

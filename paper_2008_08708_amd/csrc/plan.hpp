@@ -118,6 +118,9 @@ struct sccl_plan {
     // places staged.table there.)
     std::vector<int32_t> static_image;
     int32_t static_prog_off = 0;
+    // distinct for every plan this process creates (never reused, unlike the plan's address): names whose
+    // table the static array holds
+    uint64_t id = 0;
 };
 
 // Validates the schedule and fills everything except the device fields and `grid`.

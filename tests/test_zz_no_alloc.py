@@ -126,6 +126,36 @@ def test_repeated_calls_on_one_stream_and_bad_buffers():
     sccl.sccl_plan_destroy(pb)
 
 
+@pytest.mark.parametrize("lowering", [M, S])
+def test_one_plan_called_again_and_again(lowering):
+    """A serving loop: the same plan on new data each time.  The library writes the table only when the array does
+    not hold this plan's already, so the second and third call run on the table the first one left; a call for
+    another plan in between replaces it, and the next call brings it back."""
+    import torch
+    sf = schedule_file.load("cfg5_allreduce_torus4x4")
+    other = schedule_file.load("cfg2_allgather_hcm8")
+    epc = 4 * 37
+    plan = sccl.sccl_plan_create(*sf.descriptions("f32", epc), options={"flags": sccl.SCCL_PLAN_HOST_ONLY, "lowering": lowering})
+    plan_b = sccl.sccl_plan_create(*other.descriptions("i32", 64), options={"flags": sccl.SCCL_PLAN_HOST_ONLY})
+    hb = [inputs.generate("u32", "i32", 3, n, 0, other.positions_per_rank * 64) for n in range(8)]
+    sched = Schedule(sf.rounds, sf.sends)
+    print(f"[case] one plan again and again, lowering={lowering}", flush=True)
+    for i, seed in enumerate((31, 32, 33, 34, 35)):
+        if i == 3:                                         # another plan's table goes through the array
+            db = [torch.from_numpy(h.copy()).cuda() for h in hb]
+            sccl.sccl_execute_static(plan_b, db)
+        host = [inputs.generate("wide", "f32", seed, n, 0, sf.num_chunks * epc) for n in range(16)]
+        want = [h.copy() for h in host]
+        ex.execute("f32", sf.num_chunks, epc, sched, want)
+        got = [torch.from_numpy(h.copy()).cuda() for h in host]
+        sccl.sccl_execute_static(plan, got)
+        torch.cuda.synchronize()
+        for n in range(16):
+            assert (bits(got[n].cpu().numpy()) == bits(want[n])).all(), f"call {i}, rank {n}"
+    sccl.sccl_plan_destroy(plan)
+    sccl.sccl_plan_destroy(plan_b)
+
+
 def test_large_slices_through_the_static_entry_point():
     """A host-only staged plan whose workgroups need 128 KiB of the local data share (more than a kernel gets without
     asking): the static entry point has to ask for it itself, since the plan's creation never touched the device."""
