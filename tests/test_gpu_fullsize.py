@@ -160,3 +160,41 @@ def test_reduce_at_the_root_in_closed_form():
         for n in range(P):
             if sf.post[c, n]:
                 assert torch.equal(bufs[n].view(G, epc)[c], total.view(G, epc)[c]), f"chunk {c} at root {n}"
+
+
+@pytest.mark.parametrize("mode,lowering", [("sccl_execute", sccl.SCCL_LOWER_MEMORY), ("sccl_execute", sccl.SCCL_LOWER_STAGED),
+                                           ("sccl_execute_stepwise", 0)])
+def test_chunks_larger_than_four_gibibytes(mode, lowering):
+    """Byte offsets inside one chunk beyond 32 bits: Allreduce between two ranks, two chunks of 4 GiB + 4 MiB + 592 B
+    each (a ragged last tile), 16 GiB in all.  Two operands: the sum has the same bits in either order, so the
+    whole result is checked on the device against in_0 + in_1; the oracle checks ranges at the start of a chunk,
+    across the 4 GiB offset and at the ragged end."""
+    import torch
+    from helpers import to_binding
+    from oracle import collective as col, generate as gen, topology as tp
+    from paper_2008_08708_amd import inputs
+    topo = tp.point_to_point(2, {(0, 1): 1, (1, 0): 1}, "pair")
+    ag = col.allgather(2, 1)
+    sched, coll = gen.compose_allreduce(gen.greedy_bfs(topo, ag), ag)
+    epc = (1 << 30) + (1 << 20) + 4 * 37
+    dev = torch.device("cuda:0")
+    pristine = [inputs.torch_rank_buffer("uniform", "f32", 77, n, 2 * epc, dev) for n in range(2)]
+    work = [p.clone() for p in pristine]
+    plan = sccl.sccl_plan_create(*to_binding(topo, coll, sched, "f32", epc), options={"lowering": lowering} if lowering else None)
+    st = sccl.sccl_plan_stats(plan)
+    assert st["chunk_bytes"] > (1 << 32) and st["vector_bytes"] == 16
+    print(f"[case] chunks of {st['chunk_bytes']} bytes, {mode}, lowering={lowering}", flush=True)
+    getattr(sccl, mode)(plan, work)
+    torch.cuda.synchronize()
+    sccl.sccl_plan_destroy(plan)
+    want = pristine[0] + pristine[1]
+    for n in range(2):
+        assert torch.equal(work[n].view(torch.int32), want.view(torch.int32)), f"rank {n}"
+    del want
+    osched = Schedule(sched.rounds, sched.sends)
+    for start, count in ((0, 4096), ((1 << 30) - 2048, 4096), (epc - 4099, 4099)):
+        host = [torch.stack([p.view(2, epc)[c, start:start + count] for c in range(2)]).reshape(-1).cpu().numpy() for p in pristine]
+        ex.execute("f32", 2, count, osched, host)
+        for n in range(2):
+            got = torch.stack([work[n].view(2, epc)[c, start:start + count] for c in range(2)]).reshape(-1).cpu().numpy()
+            assert (got.view(np.uint32) == host[n].view(np.uint32)).all(), (n, start)
