@@ -17,7 +17,7 @@ class Workload:
     seed: int
     bytes_per_rank: int      # the whole rank buffer: every chunk position the layout gives a rank
     poison_non_owned: bool   # non-combining collectives: positions a rank holds nothing in at the start are undefined inputs
-    options: Optional[Dict[str, int]] = None   # launch shape found by `bench.py --workload W --sweep`, where it beats the plan's own choice
+    options: Optional[Dict[str, int]] = None   # a launch shape found by `bench.py --workload W --sweep`, where one beats the plan's own choice (none does at present)
 
     @property
     def elem_bytes(self) -> int:
@@ -38,8 +38,7 @@ WORKLOADS: Dict[str, Workload] = {
     "cfg4b": Workload("cfg4b", "cfg4b_allreduce_ring8_c2", "f16", "normal", 4, 512 * MiB, False),
     # beyond the five configurations: Alltoall, the paper's row (8,3,3) on its DGX-1 graph; 8 ranks, 8 MiB chunks
     # (a 64 MiB send buffer per rank) in a compact layout of 20 chunk positions per rank
-    # (four vectors per lane instead of the eight the plan gives copy-only schedules: 8 % faster here and only here)
-    "alltoall": Workload("alltoall", "alltoall_dgx1", "f32", "uniform", 6, 20 * 8 * MiB, True, {"vectors_per_thread": 4}),
+    "alltoall": Workload("alltoall", "alltoall_dgx1", "f32", "uniform", 6, 20 * 8 * MiB, True),
     # and the other collectives of the paper's Table 2 on the same graph, 64 MiB rank buffers
     "broadcast": Workload("broadcast", "broadcast_dgx1", "f32", "uniform", 7, 64 * MiB, True),
     "reduce": Workload("reduce", "reduce_dgx1", "f32", "uniform", 8, 64 * MiB, False),

@@ -198,8 +198,23 @@ def test_work_distribution_follows_chunk_size_and_fan_in():
     rar, rarc = gen.compose_allreduce(gen.ring_allgather(8, 4), col.allgather(8, 4))
     _, ring = plan_status(tp.ring(8), rarc, rar, "f16", (16 << 20) // 2)
     assert ring["max_fan_in"] == 1 and ring["vectors_per_thread"] == 8
+    # a copy chain (each forwarded chunk is read back by the very next write) takes 16 KiB tiles, which the L2 still
+    # holds at the next hop; with any other write in between, or a fan-out, it is 8 vectors again
+    _, chain = plan_status(tp.ring(8), col.allgather(8, 2), gen.ring_allgather(8, 2), "f32", (4 << 20) // 4)
+    assert (chain["max_fan_out"], chain["block_threads"], chain["vectors_per_thread"]) == (1, 256, 4)
+    for make in (lambda: col.gather(8, 2, 0), lambda: col.alltoall(8, 8)):
+        c = make()
+        _, st = plan_status(tp.ring(8), c, gen.greedy_route(tp.ring(8), c), "f32", (1 << 20) // 4)
+        assert st["vectors_per_thread"] == 4, c.name
+    bc = col.broadcast(8, 4, 0)                                   # both directions interleave: the distance is 2
+    _, far = plan_status(tp.ring(8), bc, gen.greedy_route(tp.ring(8), bc), "f32", (16 << 20) // 4)
+    assert (far["max_fan_out"], far["vectors_per_thread"]) == (1, 8)
+    sc = col.scatter(8, 2, 0)
+    direct = gen.greedy_route(tp.complete(8), sc)                 # one hop: nothing is read back
+    _, st = plan_status(tp.complete(8), sc, direct, "f32", (4 << 20) // 4)
+    assert st["max_chunk_groups"] == 1 and st["vectors_per_thread"] == 8
     # every choice still tiles the chunk exactly
-    for st in (tiny, big, head, ring):
+    for st in (tiny, big, head, ring, chain, far):
         tile = st["block_threads"] * st["vectors_per_thread"] * st["vector_bytes"]
         assert st["num_work_items"] == st["num_global_chunks"] * -(-st["chunk_bytes"] // tile)
 
